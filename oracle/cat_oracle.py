@@ -91,6 +91,22 @@ def head_stats(H, W, y, ignore_index=-100, slab=256, W64=None):
     return {"m": m, "lse": lse, "logq": logq, "gap": gap, "argmax": amax}
 
 
+def target_logq(H, W64, y, lse, ignore_index=-100):
+    """log q_t(y_t) = z[t, y_t] - lse_t from already known lse (0 on ignored rows).
+
+    Lets a caller that holds the y-independent statistics (lse, argmax) of a head
+    attach targets afterwards; z[t, y_t] is the plain dot product of the definition.
+    """
+    H64 = np.asarray(H, dtype=np.float64)
+    y = np.asarray(y).astype(np.int64)
+    out = np.zeros(len(y))
+    has = y != ignore_index
+    if np.any(has & ((y < 0) | (y >= W64.shape[0]))):
+        raise ValueError("target id out of range")
+    out[has] = np.sum(H64[has] * W64[y[has]], axis=1) - np.asarray(lse)[has]
+    return out
+
+
 # --------------------------------------------------------------------------
 # step 3-4: confidences and CAT weights
 # --------------------------------------------------------------------------

@@ -1,0 +1,210 @@
+"""ctypes binding of libpard2cat.so: argument marshalling only.
+
+The functions carry the C ABI's names (include/pard2_cat.h).  Tensors are torch CUDA
+tensors used purely as device-memory handles; every step of the computation runs in
+the library's HIP kernels.  There is no fallback: if the library has not been built,
+or a call returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, c_char_p, c_float, c_int32, c_int64, c_size_t, c_void_p
+from typing import Optional
+
+PARD2_BF16, PARD2_FP32 = 0, 1
+PARD2_W_CAT, PARD2_W_DECAY, PARD2_W_UNIFORM = 0, 1, 2
+PARD2_RED_MEAN_VALID, PARD2_RED_SUM = 0, 1
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat.so")
+EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
+           "pard2_cat_weights", "pard2_cat_fwd", "pard2_cat_bwd")
+
+
+class Pard2Error(RuntimeError):
+    pass
+
+
+class pard2_cat_desc(ctypes.Structure):
+    _fields_ = [("T", c_int32), ("d", c_int32), ("V", c_int32), ("B", c_int32), ("K", c_int32),
+                ("dtype", c_int32), ("weight_mode", c_int32), ("reduction", c_int32),
+                ("beta", c_float), ("gamma", c_float), ("ignore_index", c_int32), ("reserved", c_int32),
+                ("ldH", c_int64), ("ldW", c_int64)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library (once).  Raises if it is missing: there is no CPU path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise Pard2Error(f"{LIB_PATH} not found: build it with `python -m paper_2605_08632_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    D = POINTER(pard2_cat_desc)
+    L.pard2_cat_validate.argtypes = [D]
+    L.pard2_cat_validate.restype = ctypes.c_int
+    L.pard2_cat_workspace_bytes.argtypes = [D]
+    L.pard2_cat_workspace_bytes.restype = c_size_t
+    L.pard2_status_string.argtypes = [ctypes.c_int]
+    L.pard2_status_string.restype = c_char_p
+    L.pard2_cat_abi_version.argtypes = []
+    L.pard2_cat_abi_version.restype = ctypes.c_int
+    L.pard2_cat_weights.argtypes = [D, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
+    L.pard2_cat_weights.restype = ctypes.c_int
+    L.pard2_cat_fwd.argtypes = [D] + [c_void_p] * 13 + [c_void_p, c_size_t, c_void_p]
+    L.pard2_cat_fwd.restype = ctypes.c_int
+    L.pard2_cat_bwd.argtypes = [D] + [c_void_p] * 9 + [c_int32, c_void_p, c_size_t, c_void_p]
+    L.pard2_cat_bwd.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        raise Pard2Error(f"{what} failed: {lib().pard2_status_string(status).decode()} ({status})")
+
+
+def make_desc(T, d, V, B, K, dtype, weight_mode=PARD2_W_CAT, reduction=PARD2_RED_MEAN_VALID, beta=0.1,
+              gamma=1.0, ignore_index=-100, ldH=None, ldW=None) -> pard2_cat_desc:
+    return pard2_cat_desc(T, d, V, B, K, dtype, weight_mode, reduction, beta, gamma, ignore_index, 0,
+                          d if ldH is None else ldH, d if ldW is None else ldW)
+
+
+def pard2_cat_validate(desc: pard2_cat_desc) -> int:
+    return lib().pard2_cat_validate(ctypes.byref(desc))
+
+
+def pard2_cat_workspace_bytes(desc: pard2_cat_desc) -> int:
+    return lib().pard2_cat_workspace_bytes(ctypes.byref(desc))
+
+
+def pard2_status_string(status: int) -> str:
+    return lib().pard2_status_string(status).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _torch_dtype(desc):
+    import torch
+    return torch.bfloat16 if desc.dtype == PARD2_BF16 else torch.float32
+
+
+def _check_tensor(t, name, dtype, numel_min, device):
+    if t is None:
+        return
+    if not t.is_cuda or t.device != device:
+        raise Pard2Error(f"{name} must live on {device}")
+    if t.dtype != dtype:
+        raise Pard2Error(f"{name} must be {dtype}, got {t.dtype}")
+    if t.numel() < numel_min:
+        raise Pard2Error(f"{name} has {t.numel()} elements, needs {numel_min}")
+    if not t.is_contiguous() and name not in ("H", "W"):
+        raise Pard2Error(f"{name} must be contiguous")
+
+
+def alloc_workspace(desc: pard2_cat_desc, device):
+    import torch
+    n = pard2_cat_workspace_bytes(desc)
+    if n == 0:
+        _check(pard2_cat_validate(desc), "pard2_cat_validate")
+    return torch.empty(n + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_args(ws):
+    base = ws.data_ptr()
+    aligned = (base + 255) // 256 * 256
+    return aligned, ws.numel() - (aligned - base)
+
+
+def pard2_cat_weights(desc, conf, y=None, valid_len=None, w=None, exp_len=None):
+    """CAT weights (Eq.10) from given confidences.  Returns (w, exp_len)."""
+    import torch
+    dev = conf.device
+    _check_tensor(conf, "conf", torch.float32, desc.T, dev)
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
+    w = torch.empty(desc.T, dtype=torch.float32, device=dev) if w is None else w
+    exp_len = torch.empty(desc.B, dtype=torch.float32, device=dev) if exp_len is None else exp_len
+    _check_tensor(w, "w", torch.float32, desc.T, dev)
+    _check_tensor(exp_len, "exp_len", torch.float32, desc.B, dev)
+    rc = lib().pard2_cat_weights(ctypes.byref(desc), _ptr(conf), _ptr(y), _ptr(valid_len), _ptr(w), _ptr(exp_len),
+                                 _stream())
+    _check(rc, "pard2_cat_weights")
+    return w, exp_len
+
+
+def pard2_cat_fwd(desc, H, W, y, conf_in=None, valid_len=None, workspace=None, stats_only=False, out=None):
+    """Forward.  Returns a dict of device tensors: loss, lse, logp_y, w, argmax, accept_len,
+    exp_len, dev_status (loss and w are absent when stats_only)."""
+    import torch
+    dev = H.device
+    td = _torch_dtype(desc)
+    _check_tensor(H, "H", td, 0, dev)
+    _check_tensor(W, "W", td, 0, dev)
+    if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
+        raise Pard2Error("H/W strides do not match the descriptor")
+    if tuple(H.shape) != (desc.T, desc.d) or tuple(W.shape) != (desc.V, desc.d):
+        raise Pard2Error("H/W shapes do not match the descriptor")
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    _check_tensor(conf_in, "conf_in", torch.float32, desc.T, dev)
+    _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
+    ws = alloc_workspace(desc, dev) if workspace is None else workspace
+    o = {} if out is None else out
+    f32 = dict(dtype=torch.float32, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    o.setdefault("lse", torch.empty(desc.T, **f32))
+    o.setdefault("logp_y", torch.empty(desc.T, **f32))
+    o.setdefault("argmax", torch.empty(desc.T, **i32))
+    o.setdefault("accept_len", torch.empty(desc.B, **i32))
+    o.setdefault("exp_len", torch.empty(desc.B, **f32))
+    o.setdefault("dev_status", torch.empty(1, **i32))
+    if not stats_only:
+        o.setdefault("loss", torch.empty(1, **f32))
+        o.setdefault("w", torch.empty(desc.T, **f32))
+    wp, wn = _ws_args(ws)
+    rc = lib().pard2_cat_fwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(y), _ptr(conf_in), _ptr(valid_len),
+                             _ptr(o.get("loss")), _ptr(o["lse"]), _ptr(o["logp_y"]), _ptr(o.get("w")),
+                             _ptr(o["argmax"]), _ptr(o["accept_len"]), _ptr(o["exp_len"]), _ptr(o["dev_status"]),
+                             wp, wn, _stream())
+    _check(rc, "pard2_cat_fwd")
+    return o
+
+
+def pard2_cat_bwd(desc, H, W, y, lse, w, valid_len=None, grad_loss=None, dH=None, dW=None, accumulate_dW=False,
+                  workspace=None):
+    """Backward.  Returns (dH, dW)."""
+    import torch
+    dev = H.device
+    td = _torch_dtype(desc)
+    _check_tensor(H, "H", td, 0, dev)
+    _check_tensor(W, "W", td, 0, dev)
+    if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
+        raise Pard2Error("H/W strides do not match the descriptor")
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    _check_tensor(lse, "lse", torch.float32, desc.T, dev)
+    _check_tensor(w, "w", torch.float32, desc.T, dev)
+    _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
+    _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
+    dH = torch.empty(desc.T, desc.d, dtype=td, device=dev) if dH is None else dH
+    if dW is None:
+        if accumulate_dW:
+            raise Pard2Error("accumulate_dW needs an existing dW")
+        dW = torch.empty(desc.V, desc.d, dtype=td, device=dev)
+    _check_tensor(dH, "dH", td, desc.T * desc.d, dev)
+    _check_tensor(dW, "dW", td, desc.V * desc.d, dev)
+    ws = alloc_workspace(desc, dev) if workspace is None else workspace
+    wp, wn = _ws_args(ws)
+    rc = lib().pard2_cat_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(y), _ptr(valid_len), _ptr(lse), _ptr(w),
+                             _ptr(grad_loss), _ptr(dH), _ptr(dW), 1 if accumulate_dW else 0, wp, wn, _stream())
+    _check(rc, "pard2_cat_bwd")
+    return dH, dW

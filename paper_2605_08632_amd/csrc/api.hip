@@ -1,0 +1,183 @@
+// C ABI of the CAT-loss library: argument validation, workspace carving and the
+// launch sequence.  No computation happens here.
+#include "../../include/pard2_cat.h"
+
+#include "kernels.h"
+
+#include <math.h>
+#include <string.h>
+
+using namespace pard2;
+
+namespace {
+
+struct FwdPlan {
+  int P;
+  size_t off_ms, off_idx, off_zy, off_conf, off_hit, off_partials, total;
+};
+
+size_t align256(size_t x) { return (x + 255) / 256 * 256; }
+
+FwdPlan plan_fwd(const pard2_cat_desc* d) {
+  FwdPlan p{};
+  p.P = d->dtype == PARD2_BF16 ? fwd_num_partials_bf16(d->T, d->V) : fwd_num_partials_f32(d->T, d->V);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+  p.off_ms = take((size_t)d->T * p.P * sizeof(float2));
+  p.off_idx = take((size_t)d->T * p.P * sizeof(int32_t));
+  p.off_zy = take((size_t)d->T * 4);
+  p.off_conf = take((size_t)d->T * 4);
+  p.off_hit = take((size_t)d->T * 4);
+  p.off_partials = take((size_t)scan_num_groups(d->B) * 2 * sizeof(double));
+  p.total = o;
+  return p;
+}
+
+size_t bwd_bytes(const pard2_cat_desc* d) {
+  return d->dtype == PARD2_BF16 ? plan_bwd_bf16(d->T, d->d, d->V).total : plan_bwd_f32(d->T, d->d, d->V).total;
+}
+
+int check_arch() {
+  static int cached[64];  // 0 unknown, 1 ok, 2 wrong
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return PARD2_ERR_ARCH;
+  if (dev >= 0 && dev < 64 && cached[dev]) return cached[dev] == 1 ? PARD2_OK : PARD2_ERR_ARCH;
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return PARD2_ERR_ARCH;
+  const bool ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+  if (dev >= 0 && dev < 64) cached[dev] = ok ? 1 : 2;
+  return ok ? PARD2_OK : PARD2_ERR_ARCH;
+}
+
+int check_workspace(const void* ws, size_t have, size_t need) {
+  if (need == 0) return PARD2_OK;
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255) || have < need) return PARD2_ERR_WORKSPACE;
+  return PARD2_OK;
+}
+
+bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
+
+__global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
+
+}  // namespace
+
+extern "C" {
+
+int pard2_cat_abi_version(void) { return 1; }
+
+const char* pard2_status_string(int s) {
+  switch (s) {
+    case PARD2_OK: return "ok";
+    case PARD2_ERR_NULL: return "required pointer is NULL";
+    case PARD2_ERR_SHAPE: return "bad shape, stride or alignment";
+    case PARD2_ERR_DTYPE: return "unknown dtype, weight_mode or reduction";
+    case PARD2_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case PARD2_ERR_ARCH: return "device is not gfx950";
+    case PARD2_ERR_HYPER: return "bad hyper-parameter";
+    case PARD2_ERR_LAUNCH: return "HIP launch error";
+    default: return "unknown status";
+  }
+}
+
+int pard2_cat_validate(const pard2_cat_desc* d) {
+  if (!d) return PARD2_ERR_NULL;
+  if (d->dtype != PARD2_BF16 && d->dtype != PARD2_FP32) return PARD2_ERR_DTYPE;
+  if (d->weight_mode < PARD2_W_CAT || d->weight_mode > PARD2_W_UNIFORM) return PARD2_ERR_DTYPE;
+  if (d->reduction != PARD2_RED_MEAN_VALID && d->reduction != PARD2_RED_SUM) return PARD2_ERR_DTYPE;
+  if (d->T <= 0 || d->d <= 0 || d->V <= 0 || d->B <= 0 || d->K <= 0) return PARD2_ERR_SHAPE;
+  if ((int64_t)d->B * d->K != (int64_t)d->T) return PARD2_ERR_SHAPE;
+  if (d->ldH < d->d || d->ldW < d->d) return PARD2_ERR_SHAPE;
+  if (d->dtype == PARD2_BF16 && ((d->d & 7) || (d->ldH & 7) || (d->ldW & 7))) return PARD2_ERR_SHAPE;
+  // tile-relative byte offsets inside the kernels are 32-bit
+  if ((int64_t)d->ldH * 2 * 512 > 0x7fffffffLL || (int64_t)d->ldW * 2 * 512 > 0x7fffffffLL) return PARD2_ERR_SHAPE;
+  if (d->ignore_index >= 0 && d->ignore_index < d->V) return PARD2_ERR_HYPER;
+  if (!isfinite(d->beta)) return PARD2_ERR_HYPER;
+  if (d->weight_mode == PARD2_W_DECAY && !(d->gamma > 0.f && d->gamma <= 1.f)) return PARD2_ERR_HYPER;
+  return PARD2_OK;
+}
+
+size_t pard2_cat_workspace_bytes(const pard2_cat_desc* d) {
+  if (pard2_cat_validate(d) != PARD2_OK) return 0;
+  const size_t f = plan_fwd(d).total, b = bwd_bytes(d);
+  return f > b ? f : b;
+}
+
+int pard2_cat_weights(const pard2_cat_desc* d, const float* conf, const int32_t* y, const int32_t* valid_len,
+                      float* w, float* exp_len, void* stream) {
+  int rc = pard2_cat_validate(d);
+  if (rc != PARD2_OK) return rc;
+  if (!conf || !w) return PARD2_ERR_NULL;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  ScanArgs a{};
+  a.conf = conf; a.y = y; a.valid_len = valid_len; a.w = w; a.exp_len = exp_len;
+  a.B = d->B; a.K = d->K; a.V = d->V; a.ignore_index = d->ignore_index;
+  a.weight_mode = d->weight_mode; a.reduction = d->reduction; a.beta = d->beta; a.gamma = d->gamma;
+  return launch_scan(a, (hipStream_t)stream) == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
+}
+
+int pard2_cat_fwd(const pard2_cat_desc* d, const void* H, const void* W, const int32_t* y, const float* conf_in,
+                  const int32_t* valid_len, float* loss, float* lse, float* logp_y, float* w, int32_t* argmax,
+                  int32_t* accept_len, float* exp_len, int32_t* dev_status, void* workspace, size_t workspace_bytes,
+                  void* stream) {
+  int rc = pard2_cat_validate(d);
+  if (rc != PARD2_OK) return rc;
+  if (!H || !W || !y || !lse || !logp_y) return PARD2_ERR_NULL;
+  if (d->dtype == PARD2_BF16 && (misaligned16(H) || misaligned16(W))) return PARD2_ERR_SHAPE;
+  const FwdPlan p = plan_fwd(d);
+  if ((rc = check_workspace(workspace, workspace_bytes, p.total)) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  StatsOut st{(float2*)(ws + p.off_ms), (int32_t*)(ws + p.off_idx), (float*)(ws + p.off_zy), p.P};
+  float* conf = (float*)(ws + p.off_conf);
+  int32_t* hit = (int32_t*)(ws + p.off_hit);
+
+  if (dev_status) hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dev_status, 0);
+  hipError_t e = d->dtype == PARD2_BF16
+                     ? launch_fwd_stats_bf16(H, d->ldH, W, d->ldW, y, d->T, d->d, d->V, st, s)
+                     : launch_fwd_stats_f32(H, d->ldH, W, d->ldW, y, d->T, d->d, d->V, st, s);
+  if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+  e = launch_combine(st, y, conf_in, d->T, d->V, d->ignore_index, lse, logp_y, argmax, conf, hit, dev_status, s);
+  if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+  if (loss || w || accept_len || exp_len) {
+    ScanArgs a{};
+    a.conf = conf; a.y = y; a.valid_len = valid_len; a.hit = hit; a.logp_y = logp_y;
+    a.w = w; a.exp_len = exp_len; a.accept_len = accept_len; a.loss = loss;
+    a.loss_partials = (double*)(ws + p.off_partials);
+    a.B = d->B; a.K = d->K; a.V = d->V; a.ignore_index = d->ignore_index;
+    a.weight_mode = d->weight_mode; a.reduction = d->reduction; a.beta = d->beta; a.gamma = d->gamma;
+    if (launch_scan(a, s) != hipSuccess) return PARD2_ERR_LAUNCH;
+  }
+  return PARD2_OK;
+}
+
+int pard2_cat_bwd(const pard2_cat_desc* d, const void* H, const void* W, const int32_t* y, const int32_t* valid_len,
+                  const float* lse, const float* w, const float* grad_loss, void* dH, void* dW,
+                  int32_t accumulate_dW, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = pard2_cat_validate(d);
+  if (rc != PARD2_OK) return rc;
+  if (!H || !W || !y || !lse || !w || !dH || !dW) return PARD2_ERR_NULL;
+  if (d->dtype == PARD2_BF16 && (misaligned16(H) || misaligned16(W) || misaligned16(dH) || misaligned16(dW)))
+    return PARD2_ERR_SHAPE;
+  if ((rc = check_workspace(workspace, workspace_bytes, bwd_bytes(d))) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  hipError_t e;
+  if (d->dtype == PARD2_BF16) {
+    const BwdPlanBf16 p = plan_bwd_bf16(d->T, d->d, d->V);
+    float* g = (float*)(ws + p.off_g);
+    e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, d->beta, g, s);
+    if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s);
+  } else {
+    const BwdPlanF32 p = plan_bwd_f32(d->T, d->d, d->V);
+    float* g = (float*)(ws + p.off_g);
+    e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, d->beta, g, s);
+    if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+    e = launch_bwd_f32(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s);
+  }
+  return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
+}
+
+}  // extern "C"

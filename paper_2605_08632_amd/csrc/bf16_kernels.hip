@@ -1,0 +1,386 @@
+// bf16 kernels of the CAT loss on gfx950: the vocabulary-head sweep with online
+// log-softmax statistics (forward), and the split-V backward (recompute + dZ, dH, dW).
+// All four contractions run on the matrix cores through gemm_nt_mainloop.
+#include "gemm_nt_mfma.hpp"
+#include "kernels.h"
+
+#include <limits.h>
+
+namespace pard2 {
+
+static constexpr float L2E = 1.4426950408889634f;
+
+// Tile shape used by every bf16 contraction here.
+#ifndef PARD2_TILE
+#define PARD2_TILE 256, 256, 64, 4, 2
+#endif
+using Cfg = TileCfg<PARD2_TILE>;
+
+// Running softmax statistics over a set of logits: max, sum of exp(z - max), and the
+// lowest index attaining the max.
+struct RowStat {
+  float m, s;
+  int idx;
+};
+__device__ __forceinline__ RowStat merge(RowStat a, RowStat b) {
+  RowStat o;
+  o.m = fmaxf(a.m, b.m);
+  const float ms = (o.m == -INFINITY) ? 0.f : o.m;  // both empty: keep s = 0 instead of NaN
+  o.s = a.s * __builtin_amdgcn_exp2f((a.m - ms) * L2E) + b.s * __builtin_amdgcn_exp2f((b.m - ms) * L2E);
+  o.idx = (a.m > b.m) ? a.idx : (b.m > a.m) ? b.idx : min(a.idx, b.idx);
+  return o;
+}
+
+// ------------------------------------------------------------------------------------
+// Forward sweep (head contraction of Eq.4/5 + online log-softmax of the log P in Eq.11).
+// A workgroup owns BN token rows and one of `nsplit` vocabulary ranges; it walks the
+// range tile by tile (BM vocabulary rows each), and after each tile folds the BM x BN
+// logits held in registers into per-row running (max, sum, argmax).  The vocabulary is
+// on the MFMA M side, so a lane owns whole token rows: the running statistics are
+// lane-local and are merged across lanes / wavefronts only once, at the end.
+// ------------------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __restrict__ H, int64_t ldH,
+                                                                const __bf16* __restrict__ W, int64_t ldW,
+                                                                const int32_t* __restrict__ y, int T, int d, int V,
+                                                                int nTt, int nVt, int nsplit, float2* __restrict__ ms,
+                                                                int32_t* __restrict__ idx, float* __restrict__ zy) {
+  extern __shared__ __align__(16) char smem[];
+  const WavePos<C> wp;
+  int tt, sp;
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, 8, tt, sp);
+  const int n0 = tt * C::BN;
+  const int vt_begin = (int)((int64_t)sp * nVt / nsplit), vt_end = (int)((int64_t)(sp + 1) * nVt / nsplit);
+
+  RowStat run[C::NI];
+  int yt[C::NI];
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) {
+    run[ni] = {-INFINITY, 0.f, INT_MAX};
+    const int t = n0 + wp.n_of(ni);
+    yt[ni] = (t < T) ? y[t] : -1;
+  }
+
+  for (int vt = vt_begin; vt < vt_end; ++vt) {
+    const int m0 = vt * C::BM;
+    f32x16 acc[C::MI][C::NI];
+    zero_acc<C>(acc);
+    gemm_nt_mainloop<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem, acc);
+
+    const int vw0 = m0 + wp.m_of(0, 0);            // lowest vocabulary id this lane holds in the tile
+    const bool ragged = m0 + C::BM > V;
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni) {
+      if (ragged) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (m0 + wp.m_of(mi, r) >= V) acc[mi][ni][r] = -INFINITY;
+      }
+      // target logit: the lane that holds (v = y_t, t) writes it (exactly one lane in the grid)
+      const int rel = yt[ni] - (m0 + wp.wm * C::WTM);
+      if (rel >= 0 && rel < C::WTM) {
+#pragma unroll
+        for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            if (m0 + wp.m_of(mi, r) == yt[ni]) zy[n0 + wp.n_of(ni)] = acc[mi][ni][r];
+      }
+      float tmax = -INFINITY;
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) tmax = fmaxf(tmax, acc[mi][ni][r]);
+      if (tmax > run[ni].m) {  // strict: an earlier (lower) index keeps a tie
+        int best = INT_MAX;
+#pragma unroll
+        for (int mi = C::MI - 1; mi >= 0; --mi)
+#pragma unroll
+          for (int r = 15; r >= 0; --r)
+            if (acc[mi][ni][r] == tmax) best = vw0 + (wp.m_of(mi, r) - wp.m_of(0, 0));
+        run[ni].idx = best;
+      }
+      const float mnew = fmaxf(run[ni].m, tmax);
+      const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+      const float nm = -msafe * L2E;
+      float s = run[ni].s * __builtin_amdgcn_exp2f(__builtin_fmaf(run[ni].m, L2E, nm));
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mi][ni][r], L2E, nm));
+      run[ni].m = mnew;
+      run[ni].s = s;
+    }
+  }
+
+  // merge the two half-wavefronts (same rows, interleaved vocabulary ids) ...
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) {
+    RowStat o;
+    o.m = __shfl_xor(run[ni].m, 32);
+    o.s = __shfl_xor(run[ni].s, 32);
+    o.idx = __shfl_xor(run[ni].idx, 32);
+    run[ni] = merge(run[ni], o);
+  }
+  // ... then the WGM wavefronts that share the rows, through LDS (free after the main loop)
+  RowStat* sh = reinterpret_cast<RowStat*>(smem);  // [WGM][BN]
+  if (wp.lane < 32) {
+#pragma unroll
+    for (int ni = 0; ni < C::NI; ++ni) sh[wp.wm * C::BN + wp.n_of(ni)] = run[ni];
+  }
+  __syncthreads();
+  for (int n = threadIdx.x; n < C::BN; n += C::NTHREADS) {
+    RowStat a = sh[n];
+    for (int w = 1; w < C::WGM; ++w) a = merge(a, sh[w * C::BN + n]);
+    const int t = n0 + n;
+    if (t < T) {
+      ms[(int64_t)t * nsplit + sp] = make_float2(a.m, a.s);
+      idx[(int64_t)t * nsplit + sp] = a.idx;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward step 1 for one vocabulary chunk: recompute the logits tile and form
+//   dZ[t,v] = g_t * (exp(z[t,v] - lse_t) - 1[v = y_t])
+// (softmax-CE gradient scaled by the constant CAT weight, Eq.11 with the stop-gradient),
+// rounded to bf16 and written in both orientations, dZ[t][v] and dZt[v][t], so that the
+// two contractions that consume it are again NT-shaped.
+// ------------------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restrict__ H, int64_t ldH,
+                                                         const __bf16* __restrict__ W, int64_t ldW,
+                                                         const int32_t* __restrict__ y, const float* __restrict__ lse,
+                                                         const float* __restrict__ g, int T, int d, int V, int nTt,
+                                                         int vt0, int nVtc, __bf16* __restrict__ dZ, int64_t ldz,
+                                                         __bf16* __restrict__ dZt, int64_t ldzt) {
+  extern __shared__ __align__(16) char smem[];
+  const WavePos<C> wp;
+  int tt, vtl;
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, 8, tt, vtl);
+  const int n0 = tt * C::BN, m0 = (vt0 + vtl) * C::BM, c0 = vtl * C::BM;
+
+  f32x16 acc[C::MI][C::NI];
+  zero_acc<C>(acc);
+  gemm_nt_mainloop<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem, acc);
+
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) {
+    const int t = n0 + wp.n_of(ni);
+    const bool row = t < T;
+    const float gt = row ? g[t] : 0.f;
+    const float nl = row ? -lse[t] * L2E : -INFINITY;   // rows past T: q = 0
+    const int yv = row ? y[t] : -1;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int ml = wp.m_of(mi, rq * 4);           // 4 consecutive vocabulary ids from here
+        bf16x4 pk;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int v = m0 + ml + j;
+          const float z = (v < V) ? acc[mi][ni][rq * 4 + j] : -INFINITY;
+          const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(z, L2E, nl));
+          const float dz = gt * (q - ((v == yv) ? 1.f : 0.f));
+          pk[j] = (__bf16)dz;
+          dZt[(int64_t)(c0 + ml + j) * ldzt + t] = pk[j];
+        }
+        *reinterpret_cast<bf16x4*>(dZ + (int64_t)t * ldz + c0 + ml) = pk;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward step 2: dH[t,i] (+)= sum_v dZ[t,v] * W[v,i] over the chunk's vocabulary ids.
+// NT form: A = Wt (rows i, contraction v), B = dZ (rows t).  fp32 running sum across
+// chunks lives in dHacc; the last chunk writes the bf16 result.
+// ------------------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restrict__ Wt, int64_t ldWt,
+                                                         const __bf16* __restrict__ dZ, int64_t ldz, int T, int d,
+                                                         int Kc, int nIt, int nTt, float* __restrict__ dHacc,
+                                                         __bf16* __restrict__ dH, int first, int last) {
+  extern __shared__ __align__(16) char smem[];
+  const WavePos<C> wp;
+  int it, tt;
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nIt, nTt, 8, it, tt);
+  const int m0 = it * C::BM, n0 = tt * C::BN;
+
+  f32x16 acc[C::MI][C::NI];
+  zero_acc<C>(acc);
+  gemm_nt_mainloop<C>(Wt, ldWt, m0, d, dZ, ldz, n0, T, Kc, smem, acc);
+
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) {
+    const int t = n0 + wp.n_of(ni);
+    if (t >= T) continue;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int i = m0 + wp.m_of(mi, rq * 4);
+        if (i >= d) continue;
+        f32x4 v = {acc[mi][ni][rq * 4], acc[mi][ni][rq * 4 + 1], acc[mi][ni][rq * 4 + 2], acc[mi][ni][rq * 4 + 3]};
+        f32x4* p = reinterpret_cast<f32x4*>(dHacc + (int64_t)t * d + i);
+        if (!first) v += *p;
+        if (last) {
+          bf16x4 o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+          *reinterpret_cast<bf16x4*>(dH + (int64_t)t * d + i) = o;
+        } else {
+          *p = v;
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward step 3: dW[v,i] = sum_t dZ[t,v] * H[t,i] for the chunk's vocabulary rows
+// (complete per chunk: no accumulation across chunks).
+// NT form: A = Ht (rows i, contraction t), B = dZt (rows v).
+// ------------------------------------------------------------------------------------
+template <class C>
+__global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restrict__ Ht, int64_t ldHt,
+                                                         const __bf16* __restrict__ dZt, int64_t ldzt, int Tp, int d,
+                                                         int nrows, int nIt, int nVtc, __bf16* __restrict__ dWc,
+                                                         int accumulate) {
+  extern __shared__ __align__(16) char smem[];
+  const WavePos<C> wp;
+  int it, vtl;
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nIt, nVtc, 8, it, vtl);
+  const int m0 = it * C::BM, n0 = vtl * C::BN;
+
+  f32x16 acc[C::MI][C::NI];
+  zero_acc<C>(acc);
+  gemm_nt_mainloop<C>(Ht, ldHt, m0, d, dZt, ldzt, n0, nrows, Tp, smem, acc);
+
+#pragma unroll
+  for (int ni = 0; ni < C::NI; ++ni) {
+    const int vr = n0 + wp.n_of(ni);
+    if (vr >= nrows) continue;
+#pragma unroll
+    for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int i = m0 + wp.m_of(mi, rq * 4);
+        if (i >= d) continue;
+        bf16x4* p = reinterpret_cast<bf16x4*>(dWc + (int64_t)vr * d + i);
+        f32x4 v = {acc[mi][ni][rq * 4], acc[mi][ni][rq * 4 + 1], acc[mi][ni][rq * 4 + 2], acc[mi][ni][rq * 4 + 3]};
+        if (accumulate) {
+          const bf16x4 old = *p;
+          v[0] += (float)old[0]; v[1] += (float)old[1]; v[2] += (float)old[2]; v[3] += (float)old[3];
+        }
+        bf16x4 o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+        *p = o;
+      }
+  }
+}
+
+// dst[c][r] = src[r][c] for r < R, c < Ccols; dst columns R <= r < ldd are zero-filled.
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int64_t lds_, int R,
+                                                            int Ccols, uint16_t* __restrict__ dst, int64_t ldd) {
+  __shared__ uint16_t tile[64][66];
+  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  for (int j = ty; j < 64; j += 4) {
+    const int r = r0 + j, c = c0 + tx;
+    tile[j][tx] = (r < R && c < Ccols) ? src[(int64_t)r * lds_ + c] : (uint16_t)0;
+  }
+  __syncthreads();
+  for (int j = ty; j < 64; j += 4) {
+    const int c = c0 + j, r = r0 + tx;
+    if (c < Ccols && r < ldd) dst[(int64_t)c * ldd + r] = tile[tx][j];
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------
+static int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+template <class K>
+static hipError_t allow_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             Cfg::LDS_BYTES);
+}
+
+int fwd_num_partials_bf16(int T, int V) {
+  const int nTt = ceil_div(T, Cfg::BN), nVt = ceil_div(V, Cfg::BM);
+  // enough vocabulary ranges to give every compute unit a workgroup, never more than tiles
+  int ns = ceil_div(256, nTt);
+  ns = ns < 1 ? 1 : ns;
+  return ns > nVt ? nVt : ns;
+}
+
+hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const int32_t* y, int T,
+                                 int d, int V, StatsOut out, hipStream_t s) {
+  const int nTt = ceil_div(T, Cfg::BN), nVt = ceil_div(V, Cfg::BM), ns = out.P;
+  auto k = fwd_stats_kernel<Cfg>;
+  hipError_t e = allow_lds(k);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
+                     (const __bf16*)W, ldW, y, T, d, V, nTt, nVt, ns, out.ms, out.idx, out.zy);
+  return hipGetLastError();
+}
+
+BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
+  BwdPlanBf16 p{};
+  const int nVt = ceil_div(V, Cfg::BM);
+  const int max_tiles = 32;  // vocabulary tiles per chunk
+  p.nchunks = ceil_div(nVt, max_tiles);
+  p.Vc = (int64_t)ceil_div(nVt, p.nchunks) * Cfg::BM;
+  p.Tp = round_up(T, Cfg::BN);   // whole token tiles: rows T..Tp of dZ are written as zeros
+  p.ldHt = p.Tp;
+  p.ldWt = round_up(V, Cfg::BM);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
+  p.off_g = take((size_t)T * 4);
+  p.off_Wt = take((size_t)d * p.ldWt * 2);
+  p.off_Ht = take((size_t)d * p.ldHt * 2);
+  p.off_dZ = take((size_t)p.Tp * p.Vc * 2);
+  p.off_dZt = take((size_t)p.Vc * p.Tp * 2);
+  p.off_dHacc = take((size_t)T * d * 4);
+  p.total = o;
+  return p;
+}
+
+hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
+                           const int32_t* y, const float* lse, const float* g, int T, int d, int V, void* dH,
+                           void* dW, int accumulate_dW, char* ws, hipStream_t s) {
+  __bf16* Wt = (__bf16*)(ws + p.off_Wt);
+  __bf16* Ht = (__bf16*)(ws + p.off_Ht);
+  __bf16* dZ = (__bf16*)(ws + p.off_dZ);
+  __bf16* dZt = (__bf16*)(ws + p.off_dZt);
+  float* dHacc = (float*)(ws + p.off_dHacc);
+  hipError_t e;
+  if ((e = allow_lds(dz_kernel<Cfg>)) != hipSuccess) return e;
+  if ((e = allow_lds(dh_kernel<Cfg>)) != hipSuccess) return e;
+  if ((e = allow_lds(dw_kernel<Cfg>)) != hipSuccess) return e;
+
+  hipLaunchKernelGGL(transpose_pad_kernel, dim3(ceil_div(p.ldWt, 64), ceil_div(d, 64)), dim3(256), 0, s,
+                     (const uint16_t*)W, ldW, V, d, (uint16_t*)Wt, p.ldWt);
+  hipLaunchKernelGGL(transpose_pad_kernel, dim3(ceil_div(p.ldHt, 64), ceil_div(d, 64)), dim3(256), 0, s,
+                     (const uint16_t*)H, ldH, T, d, (uint16_t*)Ht, p.ldHt);
+
+  const int nVt = ceil_div(V, Cfg::BM), nTt = ceil_div(T, Cfg::BN), nIt = ceil_div(d, Cfg::BM);
+  for (int c = 0; c < p.nchunks; ++c) {
+    const int vt0 = (int)((int64_t)c * nVt / p.nchunks), vt1 = (int)((int64_t)(c + 1) * nVt / p.nchunks);
+    const int nVtc = vt1 - vt0;
+    const int v0 = vt0 * Cfg::BM;
+    const int Kc = nVtc * Cfg::BM;                 // padded chunk width (dZ columns written)
+    const int nrows = (V - v0 < Kc) ? V - v0 : Kc; // valid vocabulary rows in the chunk
+    // the dZ tiles of rows t in [T, Tp) are needed (zeros) by the dW contraction
+    const int nTtp = (int)(p.Tp / Cfg::BN);
+    hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTtp * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
+                       ldH, (const __bf16*)W, ldW, y, lse, g, T, d, V, nTtp, vt0, nVtc, dZ, p.Vc, dZt, p.Tp);
+    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, Wt + v0, p.ldWt,
+                       dZ, p.Vc, T, d, Kc, nIt, nTt, dHacc, (__bf16*)dH, c == 0, c == p.nchunks - 1);
+    hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * ceil_div(nrows, Cfg::BN)), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
+                       Ht, p.ldHt, dZt, p.Tp, (int)p.Tp, d, nrows, nIt, ceil_div(nrows, Cfg::BN),
+                       (__bf16*)dW + (int64_t)v0 * d, accumulate_dW);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace pard2

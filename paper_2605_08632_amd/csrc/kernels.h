@@ -1,0 +1,80 @@
+// Internal launch interface between the C-ABI layer and the kernel translation units.
+// Host functions only; every pointer below is a device pointer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace pard2 {
+
+inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+// Per-row, per-partial softmax statistics written by the forward sweep:
+// ms[t*P + p] = (max, sum of exp(z - max)) over the p-th vocabulary range, idx = lowest
+// index attaining that max; zy[t] = logit of the target id (written only for valid ids).
+struct StatsOut {
+  float2* ms;
+  int32_t* idx;
+  float* zy;
+  int P;
+};
+
+// number of vocabulary partials per row the forward sweep produces
+int fwd_num_partials_bf16(int T, int V);
+int fwd_num_partials_f32(int T, int V);
+
+hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const int32_t* y,
+                                 int T, int d, int V, StatsOut out, hipStream_t s);
+hipError_t launch_fwd_stats_f32(const void* H, int64_t ldH, const void* W, int64_t ldW, const int32_t* y,
+                                int T, int d, int V, StatsOut out, hipStream_t s);
+
+// Merge partials: lse, log q(y), argmax, confidence; flags out-of-range targets.
+hipError_t launch_combine(StatsOut st, const int32_t* y, const float* conf_in, int T, int V, int ignore_index,
+                          float* lse, float* logp_y, int32_t* argmax, float* conf, int32_t* hit,
+                          int32_t* dev_status, hipStream_t s);
+
+// Per-block exclusive prefix product (Eq.10) + masks + optional diagnostics and loss partials.
+struct ScanArgs {
+  const float* conf;        // [T]
+  const int32_t* y;         // [T] or null
+  const int32_t* valid_len; // [B] or null
+  const int32_t* hit;       // [T] or null
+  const float* logp_y;      // [T] or null (needed for loss)
+  float* w;                 // [T] or null
+  float* exp_len;           // [B] or null
+  int32_t* accept_len;      // [B] or null
+  float* loss;              // [1] or null
+  double* loss_partials;    // workspace [2 * scan_num_groups(B)] (needed for loss)
+  int B, K, V, ignore_index, weight_mode, reduction;
+  float beta, gamma;
+};
+int scan_num_groups(int B);
+hipError_t launch_scan(const ScanArgs& a, hipStream_t s);
+
+// g[t] = grad_loss * beta * w[t] / N on valid rows, 0 elsewhere (N from the masks).
+hipError_t launch_row_scale(const float* w, const int32_t* y, const int32_t* valid_len, const float* grad_loss,
+                            int B, int K, int V, int ignore_index, int reduction, float beta, float* g,
+                            hipStream_t s);
+
+// ---- backward, bf16 storage
+struct BwdPlanBf16 {
+  int64_t ldWt, ldHt, Tp, Vc;   // padded strides / chunk width (elements)
+  int nchunks;
+  size_t off_g, off_Wt, off_Ht, off_dZ, off_dZt, off_dHacc, total;
+};
+BwdPlanBf16 plan_bwd_bf16(int T, int d, int V);
+hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
+                           const int32_t* y, const float* lse, const float* g, int T, int d, int V,
+                           void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s);
+
+// ---- backward, fp32 storage
+struct BwdPlanF32 {
+  int64_t Vc;
+  int nchunks;
+  size_t off_g, off_dZ, total;
+};
+BwdPlanF32 plan_bwd_f32(int T, int d, int V);
+hipError_t launch_bwd_f32(const BwdPlanF32& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
+                          const int32_t* y, const float* lse, const float* g, int T, int d, int V,
+                          void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s);
+
+}  // namespace pard2

@@ -1,0 +1,189 @@
+// Bandwidth/latency-bound steps of the CAT loss: merging the per-range softmax
+// statistics, the per-block prefix product of confidences (Eq.10), the weighted
+// reduction of Eq.11 and the per-row gradient scale of the backward.
+#include "kernels.h"
+
+#include <limits.h>
+
+namespace pard2 {
+
+// ---------------------------------------------------------------- combine partial statistics
+// One thread per token row: (max, sumexp, argmax) over all vocabulary ranges ->
+// lse, log q_t(y_t) (log P of Eq.5/Eq.11), greedy prediction, confidence (Eq.9: given,
+// or q_t(y_t) in the self-teacher instance).
+__global__ __launch_bounds__(256) void combine_kernel(const float2* __restrict__ ms, const int32_t* __restrict__ idx,
+                                                      const float* __restrict__ zy, int P,
+                                                      const int32_t* __restrict__ y, const float* __restrict__ conf_in,
+                                                      int T, int V, int ignore_index, float* __restrict__ lse,
+                                                      float* __restrict__ logp_y, int32_t* __restrict__ argmax,
+                                                      float* __restrict__ conf, int32_t* __restrict__ hit,
+                                                      int32_t* __restrict__ dev_status) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float2* p = ms + (int64_t)t * P;
+  const int32_t* pi = idx + (int64_t)t * P;
+  float m = -INFINITY;
+  int am = INT_MAX;
+  for (int j = 0; j < P; ++j) {
+    const float mj = p[j].x;
+    if (mj > m) {  // ranges ascend in vocabulary id: the first range attaining the max has the lowest index
+      m = mj;
+      am = pi[j];
+    }
+  }
+  float s = 0.f;
+  for (int j = 0; j < P; ++j) s += p[j].y * expf(p[j].x - m);
+  const float l = m + logf(s);
+  const int yv = y[t];
+  const bool ok = yv >= 0 && yv < V;
+  if (!ok && yv != ignore_index && dev_status) *dev_status = 1;
+  const float lp = ok ? zy[t] - l : 0.f;
+  lse[t] = l;
+  logp_y[t] = lp;
+  if (argmax) argmax[t] = am;
+  if (conf) conf[t] = conf_in ? conf_in[t] : (ok ? expf(lp) : 1.f);
+  if (hit) hit[t] = ok && am == yv;
+}
+
+hipError_t launch_combine(StatsOut st, const int32_t* y, const float* conf_in, int T, int V, int ignore_index,
+                          float* lse, float* logp_y, int32_t* argmax, float* conf, int32_t* hit,
+                          int32_t* dev_status, hipStream_t s) {
+  hipLaunchKernelGGL(combine_kernel, dim3((T + 255) / 256), dim3(256), 0, s, st.ms, st.idx, st.zy, st.P, y, conf_in,
+                     T, V, ignore_index, lse, logp_y, argmax, conf, hit, dev_status);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- per-block scan
+// One thread per draft block walks its K slots left to right:
+//   s_0 = 1, s_k = s_{k-1} * c_{k-1}   (Eq.10), or gamma^k / 1 for the comparators,
+// masks invalid slots, and collects the block's diagnostics and its share of
+// sum_t w_t * (-log q_t(y_t)).  Block shares are reduced in a fixed order (LDS tree per
+// workgroup, then one workgroup over the group partials): the loss is reproducible.
+constexpr int SCAN_THREADS = 256;
+int scan_num_groups(int B) { return (B + SCAN_THREADS - 1) / SCAN_THREADS; }
+
+__global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a) {
+  __shared__ double sh_sum[SCAN_THREADS];
+  __shared__ double sh_cnt[SCAN_THREADS];
+  const int b = blockIdx.x * SCAN_THREADS + threadIdx.x;
+  double lsum = 0.0, cnt = 0.0;
+  if (b < a.B) {
+    const int K = a.K;
+    int Kb = a.valid_len ? a.valid_len[b] : K;
+    Kb = max(0, min(Kb, K));
+    float run = 1.f, gpow = 1.f, el = 0.f;
+    int al = 0;
+    bool prefix = true;
+    for (int k = 0; k < K; ++k) {
+      const int64_t t = (int64_t)b * K + k;
+      const float c = a.conf[t];
+      const float s = (a.weight_mode == 0) ? run : (a.weight_mode == 1) ? gpow : 1.f;
+      bool has = true;
+      if (a.y) {
+        const int yv = a.y[t];
+        has = yv >= 0 && yv < a.V;
+      }
+      const bool in = k < Kb;
+      const bool valid = in && has;
+      const float wv = valid ? s : 0.f;
+      if (a.w) a.w[t] = wv;
+      if (in) el += s * c;
+      if (a.hit) {
+        prefix = prefix && in && a.hit[t] != 0;
+        al += prefix ? 1 : 0;
+      }
+      if (valid && a.logp_y) {
+        lsum += (double)wv * (double)(-a.logp_y[t]);
+        cnt += 1.0;
+      }
+      run *= c;
+      gpow *= a.gamma;
+    }
+    if (a.exp_len) a.exp_len[b] = el;
+    if (a.accept_len) a.accept_len[b] = al;
+  }
+  if (!a.loss) return;
+  sh_sum[threadIdx.x] = lsum;
+  sh_cnt[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int s = SCAN_THREADS / 2; s > 0; s >>= 1) {
+    if (threadIdx.x < s) {
+      sh_sum[threadIdx.x] += sh_sum[threadIdx.x + s];
+      sh_cnt[threadIdx.x] += sh_cnt[threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    a.loss_partials[2 * blockIdx.x] = sh_sum[0];
+    a.loss_partials[2 * blockIdx.x + 1] = sh_cnt[0];
+  }
+}
+
+__global__ __launch_bounds__(64) void loss_finalize_kernel(const double* __restrict__ partials, int ngroups,
+                                                           int reduction, float beta, float* __restrict__ loss) {
+  if (threadIdx.x != 0) return;
+  double sum = 0.0, cnt = 0.0;
+  for (int i = 0; i < ngroups; ++i) {
+    sum += partials[2 * i];
+    cnt += partials[2 * i + 1];
+  }
+  double l;
+  if (reduction == 0)
+    l = cnt > 0.0 ? (double)beta * sum / cnt : 0.0;
+  else
+    l = (double)beta * sum;
+  *loss = (float)l;
+}
+
+hipError_t launch_scan(const ScanArgs& a, hipStream_t s) {
+  const int groups = scan_num_groups(a.B);
+  hipLaunchKernelGGL(scan_kernel, dim3(groups), dim3(SCAN_THREADS), 0, s, a);
+  if (a.loss)
+    hipLaunchKernelGGL(loss_finalize_kernel, dim3(1), dim3(64), 0, s, a.loss_partials, groups, a.reduction, a.beta,
+                       a.loss);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- backward row scale
+// g_t = grad_loss * beta * w_t / N on valid rows (N = number of valid tokens for
+// MEAN_VALID, 1 for SUM), 0 on invalid rows.  Single workgroup: T is at most a few 10^4.
+__global__ __launch_bounds__(1024) void row_scale_kernel(const float* __restrict__ w, const int32_t* __restrict__ y,
+                                                         const int32_t* __restrict__ valid_len,
+                                                         const float* __restrict__ grad_loss, int B, int K, int V,
+                                                         int reduction, float beta, float* __restrict__ g) {
+  __shared__ int sh[1024];
+  const int64_t T = (int64_t)B * K;
+  auto valid = [&](int64_t t) {
+    const int b = (int)(t / K), k = (int)(t % K);
+    const int Kb = valid_len ? valid_len[b] : K;
+    const int yv = y[t];
+    return k < Kb && yv >= 0 && yv < V;
+  };
+  int cnt = 0;
+  for (int64_t t = threadIdx.x; t < T; t += blockDim.x) cnt += valid(t) ? 1 : 0;
+  sh[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) sh[threadIdx.x] += sh[threadIdx.x + s];
+    __syncthreads();
+  }
+  const int n = sh[0];
+  const float go = grad_loss ? *grad_loss : 1.f;
+  float scale;
+  if (reduction == 0)
+    scale = n > 0 ? go * beta / (float)n : 0.f;
+  else
+    scale = go * beta;
+  for (int64_t t = threadIdx.x; t < T; t += blockDim.x) g[t] = valid(t) ? scale * w[t] : 0.f;
+}
+
+hipError_t launch_row_scale(const float* w, const int32_t* y, const int32_t* valid_len, const float* grad_loss,
+                            int B, int K, int V, int ignore_index, int reduction, float beta, float* g,
+                            hipStream_t s) {
+  (void)ignore_index;  // ignore_index is outside [0, V) by validation: the range test covers it
+  hipLaunchKernelGGL(row_scale_kernel, dim3(1), dim3(1024), 0, s, w, y, valid_len, grad_loss, B, K, V, reduction,
+                     beta, g);
+  return hipGetLastError();
+}
+
+}  // namespace pard2

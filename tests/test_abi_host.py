@@ -1,0 +1,104 @@
+"""Host-only checks of the C-ABI library: it loads, exports every function the public
+header declares, and its pure host helpers (validation, workspace sizing, status strings)
+behave.  No GPU compute call is made here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2605_08632_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_08632_amd import build
+        build.build(verbose=False)
+    return binding
+
+
+def _declared_functions():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(pard2_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol(b):
+    L = b.lib()
+    declared = _declared_functions()
+    assert {"pard2_cat_fwd", "pard2_cat_bwd", "pard2_cat_weights"} <= declared
+    for name in declared:
+        assert hasattr(L, name), f"{name} declared in include/ but not exported"
+    assert set(b.EXPORTS) == declared
+    assert L.pard2_cat_abi_version() == 1
+
+
+def test_descriptor_layout_matches_header(b):
+    # 12 four-byte fields then two int64: 64 bytes, strides at offsets 48 and 56
+    assert ctypes.sizeof(b.pard2_cat_desc) == 64
+    assert b.pard2_cat_desc.ldH.offset == 48 and b.pard2_cat_desc.ldW.offset == 56
+
+
+def test_validate_and_workspace(b):
+    ok = b.make_desc(8192, 2048, 128256, 1024, 8, b.PARD2_BF16)
+    assert b.pard2_cat_validate(ok) == 0
+    n = b.pard2_cat_workspace_bytes(ok)
+    assert 0 < n < 8 << 30
+    # never the T x V logits: far below T*V*2 bytes
+    assert n < 8192 * 128256 * 2
+    bad = [
+        (dict(T=8191), -2),                      # T != B*K
+        (dict(d=2044, ldH=2044, ldW=2044), -2),  # bf16 needs d % 8 == 0
+        (dict(ldH=2040), -2),                    # stride below d
+        (dict(dtype=7), -3),
+        (dict(weight_mode=3), -3),
+        (dict(reduction=2), -3),
+        (dict(beta=float("nan")), -6),
+        (dict(weight_mode=b.PARD2_W_DECAY, gamma=0.0), -6),
+        (dict(weight_mode=b.PARD2_W_DECAY, gamma=1.5), -6),
+        (dict(ignore_index=5), -6),              # ignore_index must not be a real id
+        (dict(V=0), -2),
+    ]
+    for change, code in bad:
+        d = b.make_desc(8192, 2048, 128256, 1024, 8, b.PARD2_BF16)
+        for k, v in change.items():
+            setattr(d, k, v)
+        assert b.pard2_cat_validate(d) == code, change
+        assert b.pard2_cat_workspace_bytes(d) == 0
+    assert b.lib().pard2_cat_validate(None) == -1
+    f32 = b.make_desc(64, 250, 4099, 8, 8, b.PARD2_FP32)          # fp32 has no multiple-of-8 rule
+    assert b.pard2_cat_validate(f32) == 0 and b.pard2_cat_workspace_bytes(f32) > 0
+
+
+def test_status_strings(b):
+    seen = {b.pard2_status_string(c) for c in range(0, -8, -1)}
+    assert len(seen) == 8 and "ok" in seen
+    assert "unknown" in b.pard2_status_string(-99)
+
+
+def test_null_arguments_rejected_before_any_launch(b):
+    L = b.lib()
+    d = b.make_desc(64, 256, 4096, 8, 8, b.PARD2_FP32)
+    args = [ctypes.byref(d)] + [None] * 13 + [None, 0, None]
+    assert L.pard2_cat_fwd(*args) == -1
+    args = [ctypes.byref(d)] + [None] * 9 + [0, None, 0, None]
+    assert L.pard2_cat_bwd(*args) == -1
+    assert L.pard2_cat_weights(ctypes.byref(d), None, None, None, None, None, None) == -1
+    # non-null data pointers but no workspace -> workspace error (still no launch)
+    one = ctypes.c_void_p(256)
+    args = [ctypes.byref(d)] + [one] * 3 + [None, None, one, one, one, one, None, None, None, None] + [None, 0, None]
+    assert L.pard2_cat_fwd(*args) == -4
+
+
+def test_binding_raises_without_library(b, monkeypatch, tmp_path):
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(b.Pard2Error):
+        b.lib()

@@ -1,0 +1,215 @@
+"""HIP path vs fp64 oracle, element by element, through the C ABI (ctypes binding).
+
+Sizes here are ones the oracle finishes in seconds; they span several MFMA tiles with
+ragged tails in every dimension.  Full-size workloads are in test_gpu_fullsize.py.
+"""
+import numpy as np
+import pytest
+
+from oracle import cat_oracle as O
+from tests import helpers as Hh
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _binding():
+    from paper_2605_08632_amd import binding
+    return binding
+
+
+def _run_case(p, beta=0.1, mode=O.W_CAT, gamma=1.0, reduction=O.RED_MEAN_VALID, external=False,
+              grad_loss=None, check_bwd=True):
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    dt = b.PARD2_BF16 if p.dtype == "bf16" else b.PARD2_FP32
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, dt, weight_mode=mode, reduction=reduction, beta=beta,
+                       gamma=gamma)
+    ws = b.alloc_workspace(desc, H.device)
+    gamma32 = float(np.float32(gamma))
+    beta32 = float(np.float32(beta))
+    ref = Hh.oracle_forward(p, conf_in=p.conf_ext if external else None, mode=mode, gamma=gamma32,
+                            beta=beta32, reduction=reduction)
+    out = b.pard2_cat_fwd(desc, H, W, y, conf_in=conf if external else None, valid_len=vl, workspace=ws)
+    Hh.check_forward(out, ref, p)
+    if not check_bwd:
+        return
+    gout = 1.0 if grad_loss is None else grad_loss
+    g = O.row_scale(ref["w"], beta32, ref["n_valid"], reduction, gout)
+    rb = O.cat_backward(p.head.H, None, p.y, ref["lse"], g, W64=p.W64)
+    gl = None if grad_loss is None else torch.tensor([grad_loss], dtype=torch.float32, device=H.device)
+    dH, dW = b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"], valid_len=vl, grad_loss=gl, workspace=ws)
+    torch.cuda.synchronize()
+    eH, eW = Hh.check_grads(dH, dW, rb["dH"], rb["dW"], p.dtype)
+    # invalid rows carry exactly zero gradient
+    inv = ~O.valid_mask(p.y, p.B, p.K, p.valid_len)
+    if inv.any():
+        assert not dH.float().cpu().numpy()[inv].any()
+    return eH, eW
+
+
+# ---------------------------------------------------------------- fp32 tiny workload
+@pytest.fixture(scope="module")
+def c0():
+    return Hh.build_problem(8, 8, 256, 4096, "fp32", seed=20260508, p_agree=0.6)
+
+
+@pytest.mark.parametrize("variant", ["cat_beta0.1", "cat_beta1", "decay1", "decay0.8", "uniform", "external",
+                                     "sum", "gradloss"])
+def test_c0_fp32(c0, variant):
+    kw = {
+        "cat_beta0.1": dict(beta=0.1),
+        "cat_beta1": dict(beta=1.0),
+        "decay1": dict(mode=O.W_DECAY, gamma=1.0),
+        "decay0.8": dict(mode=O.W_DECAY, gamma=0.8),
+        "uniform": dict(mode=O.W_UNIFORM),
+        "external": dict(external=True),
+        "sum": dict(reduction=O.RED_SUM, beta=1.0),
+        "gradloss": dict(grad_loss=3.5),
+    }[variant]
+    _run_case(c0, **kw)
+
+
+def test_fp32_ragged_shapes():
+    # nothing divides the 64-wide tiles; valid_len and dropped slots present
+    p = Hh.build_problem(13, 5, 100, 1001, "fp32", seed=11, ragged_frac=0.3, drop_some=True)
+    _run_case(p, beta=0.5)
+    _run_case(p, beta=0.5, external=True)
+
+
+# ---------------------------------------------------------------- bf16 MFMA path
+@pytest.fixture(scope="module")
+def bf_ragged():
+    # T = 296 (one full 256-row tile + ragged), d = 200 (k tail of 8), V = 1000 (ragged 4th tile)
+    return Hh.build_problem(37, 8, 200, 1000, "bf16", seed=21, ragged_frac=0.2, drop_some=True)
+
+
+@pytest.mark.parametrize("variant", ["self", "external", "uniform_sum"])
+def test_bf16_ragged(bf_ragged, variant):
+    kw = {"self": dict(beta=1.0), "external": dict(external=True),
+          "uniform_sum": dict(mode=O.W_UNIFORM, reduction=O.RED_SUM, beta=0.1)}[variant]
+    _run_case(bf_ragged, **kw)
+
+
+def test_bf16_multi_tile_k16():
+    # several token tiles and vocabulary tiles, K = 16 blocks with decaying agreement
+    p = Hh.build_problem(40, 16, 512, 3000, "bf16", seed=22, p_agree=("linear", 0.9, 0.3))
+    _run_case(p)
+
+
+def test_bf16_small_t():
+    # fewer rows than one tile, d below one k step
+    p = Hh.build_problem(3, 4, 32, 700, "bf16", seed=23)
+    _run_case(p, beta=1.0)
+
+
+def test_c1_small_bf16():
+    """T = 2048 (256 x 8), d = 2048, V = 32000: forward only (stats), then forward + backward."""
+    p = Hh.build_problem(256, 8, 2048, 32000, "bf16", seed=20260509, p_agree=0.6)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=0.1)
+    ref = Hh.oracle_forward(p, beta=float(np.float32(0.1)))
+    out = b.pard2_cat_fwd(desc, H, W, y, stats_only=True)
+    Hh.check_forward(out, ref, p, stats_only=True)
+    assert "loss" not in out
+    _run_case(p)
+
+
+# ---------------------------------------------------------------- edge cases
+def test_k_equals_one_is_plain_ce():
+    p = Hh.build_problem(48, 1, 64, 512, "fp32", seed=31)
+    _run_case(p, beta=1.0)
+
+
+def test_all_rows_ignored():
+    p = Hh.build_problem(4, 4, 64, 512, "bf16", seed=32)
+    p.y = np.full(p.T, -100, dtype=np.int32)
+    p.stats["logq"] = np.zeros(p.T)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0)
+    out = b.pard2_cat_fwd(desc, H, W, y)
+    assert out["loss"].item() == 0.0 and not out["w"].any().item()
+    assert not out["accept_len"].any().item()
+    dH, dW = b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"])
+    assert not dH.float().any().item() and not dW.float().any().item()
+
+
+def test_out_of_range_target_sets_dev_status():
+    p = Hh.build_problem(4, 4, 64, 512, "fp32", seed=33)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    y = y.clone()
+    y[5] = p.V + 3
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_FP32, beta=1.0)
+    out = b.pard2_cat_fwd(desc, H, W, y)
+    assert out["dev_status"].item() == 1
+    assert out["w"][5].item() == 0.0
+    # the row behaves as ignored: same loss as the oracle with that slot dropped
+    p.y = p.y.copy()
+    p.y[5] = -100
+    p.stats["logq"][5] = 0.0
+    ref = Hh.oracle_forward(p, beta=1.0)
+    assert abs(out["loss"].item() - ref["loss"]) < 2e-3 * abs(ref["loss"])
+
+
+def test_weights_entry_point():
+    b = _binding()
+    rng = np.random.default_rng(34)
+    B, K = 300, 16
+    conf = rng.random(B * K).astype(np.float32)
+    conf[rng.random(B * K) < 0.02] = 0.0               # zero confidence switches off the tail
+    vl = rng.integers(0, K + 1, B).astype(np.int32)
+    y = rng.integers(0, 50, B * K).astype(np.int32)
+    y[rng.random(B * K) < 0.1] = -100
+    for mode, gamma in [(O.W_CAT, 1.0), (O.W_DECAY, 0.8), (O.W_UNIFORM, 1.0)]:
+        desc = b.make_desc(B * K, 8, 50, B, K, b.PARD2_FP32, weight_mode=mode, gamma=gamma)
+        w, el = b.pard2_cat_weights(desc, torch.from_numpy(conf).cuda(), torch.from_numpy(y).cuda(),
+                                    torch.from_numpy(vl).cuda())
+        s, e = O.cat_weights(conf, B, K, vl, mode, float(np.float32(gamma)))
+        ref_w = np.where(O.valid_mask(y, B, K, vl), s, 0.0)
+        np.testing.assert_allclose(w.cpu().numpy(), ref_w, rtol=2e-6, atol=0)
+        np.testing.assert_allclose(el.cpu().numpy(), e, rtol=2e-6, atol=1e-7)
+        # range and monotonicity along the prefix (Eq.10 with probabilities)
+        if mode == O.W_CAT:
+            desc2 = b.make_desc(B * K, 8, 50, B, K, b.PARD2_FP32)
+            w2, _ = b.pard2_cat_weights(desc2, torch.from_numpy(conf).cuda())
+            w2 = w2.cpu().numpy().reshape(B, K)
+            assert np.all(w2[:, 0] == 1) and np.all(np.diff(w2, axis=1) <= 0) and np.all(w2 >= 0)
+
+
+def test_accumulate_dw_and_determinism():
+    p = Hh.build_problem(24, 8, 128, 900, "bf16", seed=35)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0)
+    out = b.pard2_cat_fwd(desc, H, W, y)
+    dH1, dW1 = b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"])
+    dH2, dW2 = b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"])
+    assert torch.equal(dH1, dH2) and torch.equal(dW1, dW2)          # bitwise reproducible
+    base = torch.randn_like(dW1.float()).mul_(dW1.float().abs().max()).to(torch.bfloat16)
+    acc = base.clone()
+    b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"], dW=acc, accumulate_dW=True)
+    expect = base.float() + dW1.float()
+    err = (acc.float() - expect).abs().max().item() / expect.abs().max().item()
+    assert err < 1e-2
+
+
+def test_strided_inputs():
+    p = Hh.build_problem(6, 8, 64, 520, "bf16", seed=36)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    Hs = torch.zeros(p.T, p.d + 24, dtype=H.dtype, device=H.device)
+    Ws = torch.zeros(p.V, p.d + 8, dtype=W.dtype, device=W.device)
+    Hs[:, :p.d] = H
+    Ws[:, :p.d] = W
+    d1 = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0)
+    d2 = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0, ldH=p.d + 24, ldW=p.d + 8)
+    o1 = b.pard2_cat_fwd(d1, H, W, y)
+    o2 = b.pard2_cat_fwd(d2, Hs[:, :p.d], Ws[:, :p.d], y)
+    assert torch.equal(o1["lse"], o2["lse"]) and torch.equal(o1["loss"], o2["loss"])
+    g1 = b.pard2_cat_bwd(d1, H, W, y, o1["lse"], o1["w"])
+    g2 = b.pard2_cat_bwd(d2, Hs[:, :p.d], Ws[:, :p.d], y, o2["lse"], o2["w"])
+    assert torch.equal(g1[0], g2[0]) and torch.equal(g1[1], g2[1])

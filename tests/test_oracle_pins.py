@@ -335,3 +335,15 @@ def test_out_of_range_target_raises():
     H, W, y = tiny_problem(15, 1, 4, 5, 9)
     with pytest.raises(ValueError):
         O.head_stats(H, W, [0, 9, 1, 2])
+
+
+def test_target_logq_matches_head_stats():
+    H, W, y = tiny_problem(16, B=3, K=4, d=6, V=21)
+    y = y.copy()
+    y[5] = -100
+    st = O.head_stats(H, W, y)
+    lq = O.target_logq(H, W.astype(np.float64), y, st["lse"])
+    np.testing.assert_allclose(lq, st["logq"], atol=1e-14)
+    Z = np.einsum("ti,vi->tv", H, W)
+    ok = y >= 0
+    np.testing.assert_allclose(lq[ok], log_softmax(Z, axis=1)[np.arange(12)[ok], y[ok]], atol=1e-13)
