@@ -132,6 +132,16 @@ int pard2_cat_bwd(const pard2_cat_desc* desc, const void* H, const void* W, cons
                   const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* Measurement aid (not part of the method).  pard2_cat_kernel_timing(1) makes every later
+ * launch of the four contraction kernels record a pair of HIP events on its stream;
+ * pard2_cat_kernel_timing(0) switches it off; either call forgets earlier records.
+ * pard2_cat_kernel_timing_read waits for the recorded launches of one kernel
+ * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW) and returns their summed duration in
+ * milliseconds and their count.  Host pointers.  Not thread-safe against concurrent
+ * launches from other host threads. */
+int pard2_cat_kernel_timing(int enable);
+int pard2_cat_kernel_timing_read(int kernel, double* total_ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

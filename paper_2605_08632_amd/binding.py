@@ -18,7 +18,9 @@ PARD2_RED_MEAN_VALID, PARD2_RED_SUM = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat.so")
 EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
-           "pard2_cat_weights", "pard2_cat_fwd", "pard2_cat_bwd")
+           "pard2_cat_weights", "pard2_cat_fwd", "pard2_cat_bwd", "pard2_cat_kernel_timing",
+           "pard2_cat_kernel_timing_read")
+KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel")
 
 
 class Pard2Error(RuntimeError):
@@ -58,8 +60,24 @@ def lib() -> ctypes.CDLL:
     L.pard2_cat_fwd.restype = ctypes.c_int
     L.pard2_cat_bwd.argtypes = [D] + [c_void_p] * 9 + [c_int32, c_void_p, c_size_t, c_void_p]
     L.pard2_cat_bwd.restype = ctypes.c_int
+    L.pard2_cat_kernel_timing.argtypes = [ctypes.c_int]
+    L.pard2_cat_kernel_timing.restype = ctypes.c_int
+    L.pard2_cat_kernel_timing_read.argtypes = [ctypes.c_int, POINTER(ctypes.c_double), POINTER(c_int64)]
+    L.pard2_cat_kernel_timing_read.restype = ctypes.c_int
     _lib = L
     return L
+
+
+def pard2_cat_kernel_timing(enable: bool) -> None:
+    _check(lib().pard2_cat_kernel_timing(1 if enable else 0), "pard2_cat_kernel_timing")
+
+
+def pard2_cat_kernel_timing_read(kernel: int):
+    """(total milliseconds, launch count) of the recorded launches of one contraction kernel."""
+    ms, n = ctypes.c_double(0), c_int64(0)
+    _check(lib().pard2_cat_kernel_timing_read(kernel, ctypes.byref(ms), ctypes.byref(n)),
+           "pard2_cat_kernel_timing_read")
+    return ms.value, n.value
 
 
 def _check(status: int, what: str) -> None:

@@ -7,7 +7,41 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 using namespace pard2;
+
+// ---- optional per-kernel event timing -------------------------------------------------
+namespace pard2 {
+namespace {
+struct TimedLaunch {
+  int id;
+  hipEvent_t start, stop;
+};
+bool g_timing = false;
+std::mutex g_timing_mu;
+std::vector<TimedLaunch> g_launches;
+}  // namespace
+
+void kt_begin(int id, hipStream_t s) {
+  if (!g_timing) return;
+  TimedLaunch t{id, nullptr, nullptr};
+  if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return;
+  (void)hipEventRecord(t.start, s);
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  g_launches.push_back(t);
+}
+void kt_end(int id, hipStream_t s) {
+  if (!g_timing) return;
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (size_t i = g_launches.size(); i-- > 0;)
+    if (g_launches[i].id == id) {
+      (void)hipEventRecord(g_launches[i].stop, s);
+      return;
+    }
+}
+}  // namespace pard2
 
 namespace {
 
@@ -64,6 +98,36 @@ __global__ void set_i32_kernel(int32_t* p, int32_t v) { *p = v; }
 extern "C" {
 
 int pard2_cat_abi_version(void) { return 1; }
+
+int pard2_cat_kernel_timing(int enable) {
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  for (auto& t : g_launches) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  g_launches.clear();
+  g_timing = enable != 0;
+  return PARD2_OK;
+}
+
+int pard2_cat_kernel_timing_read(int kernel, double* total_ms, int64_t* launches) {
+  if (!total_ms || !launches) return PARD2_ERR_NULL;
+  if (kernel < 0 || kernel >= KT_COUNT) return PARD2_ERR_SHAPE;
+  std::lock_guard<std::mutex> lk(g_timing_mu);
+  double sum = 0.0;
+  int64_t n = 0;
+  for (auto& t : g_launches) {
+    if (t.id != kernel) continue;
+    if (hipEventSynchronize(t.stop) != hipSuccess) return PARD2_ERR_LAUNCH;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, t.start, t.stop) != hipSuccess) return PARD2_ERR_LAUNCH;
+    sum += ms;
+    ++n;
+  }
+  *total_ms = sum;
+  *launches = n;
+  return PARD2_OK;
+}
 
 const char* pard2_status_string(int s) {
   switch (s) {

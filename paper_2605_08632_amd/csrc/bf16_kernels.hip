@@ -319,8 +319,10 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
   auto k = fwd_stats_kernel<Cfg>;
   hipError_t e = allow_lds(k);
   if (e != hipSuccess) return e;
+  kt_begin(KT_FWD_STATS, s);
   hipLaunchKernelGGL(k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
                      (const __bf16*)W, ldW, y, T, d, V, nTt, nVt, ns, out.ms, out.idx, out.zy);
+  kt_end(KT_FWD_STATS, s);
   return hipGetLastError();
 }
 
@@ -372,13 +374,19 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     const int nrows = (V - v0 < Kc) ? V - v0 : Kc; // valid vocabulary rows in the chunk
     // the dZ tiles of rows t in [T, Tp) are needed (zeros) by the dW contraction
     const int nTtp = (int)(p.Tp / Cfg::BN);
+    kt_begin(KT_DZ, s);
     hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTtp * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
                        ldH, (const __bf16*)W, ldW, y, lse, g, T, d, V, nTtp, vt0, nVtc, dZ, p.Vc, dZt, p.Tp);
+    kt_end(KT_DZ, s);
+    kt_begin(KT_DH, s);
     hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, Wt + v0, p.ldWt,
                        dZ, p.Vc, T, d, Kc, nIt, nTt, dHacc, (__bf16*)dH, c == 0, c == p.nchunks - 1);
+    kt_end(KT_DH, s);
+    kt_begin(KT_DW, s);
     hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * ceil_div(nrows, Cfg::BN)), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
                        Ht, p.ldHt, dZt, p.Tp, (int)p.Tp, d, nrows, nIt, ceil_div(nrows, Cfg::BN),
                        (__bf16*)dW + (int64_t)v0 * d, accumulate_dW);
+    kt_end(KT_DW, s);
   }
   return hipGetLastError();
 }

@@ -8,6 +8,13 @@ namespace pard2 {
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
+// Optional per-kernel timing (off by default): when switched on through
+// pard2_cat_kernel_timing(), every launch of one of the four contraction kernels is
+// bracketed by a pair of HIP events on its stream.
+enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_COUNT = 4 };
+void kt_begin(int id, hipStream_t s);
+void kt_end(int id, hipStream_t s);
+
 // Per-row, per-partial softmax statistics written by the forward sweep:
 // ms[t*P + p] = (max, sum of exp(z - max)) over the p-th vocabulary range, idx = lowest
 // index attaining that max; zy[t] = logit of the target id (written only for valid ids).

@@ -94,16 +94,28 @@ class Head:
     dtype: str = "fp32"
 
 
-def make_head(seed: int, T: int, d: int, V: int, dtype: str, w_scale: float = 4.0) -> Head:
+def _unit_rms_rows(H: np.ndarray) -> np.ndarray:
+    rms = np.sqrt(np.mean(H.astype(np.float64) ** 2, axis=1, keepdims=True))
+    return (H / rms).astype(np.float32)
+
+
+def make_head(seed: int, T: int, d: int, V: int, dtype: str, w_scale: float = 4.0,
+              row_attempts: Optional[np.ndarray] = None) -> Head:
     """H ~ N(0,1) with every row scaled to RMS 1; W ~ N(0, 1/d) * w_scale.
 
     With unit-RMS rows the logits have standard deviation ~ w_scale: a peaked
-    but non-degenerate softmax.
+    but non-degenerate softmax.  `row_attempts[t] = a > 0` replaces row t of H by
+    the a-th re-draw of that row (its own seeded stream): callers use it to move a
+    row whose two largest logits nearly tie, where "the" argmax is not well-posed
+    under reordered fp32 accumulation.
     """
     rng = np.random.default_rng([seed, 0])
     H = rng.standard_normal((T, d), dtype=np.float32)
-    rms = np.sqrt(np.mean(H.astype(np.float64) ** 2, axis=1, keepdims=True))
-    H = (H / rms).astype(np.float32)
+    if row_attempts is not None:
+        for t in np.nonzero(row_attempts)[0]:
+            r = np.random.default_rng([seed, 7, int(t), int(row_attempts[t])])
+            H[t] = r.standard_normal(d, dtype=np.float32)
+    H = _unit_rms_rows(H)
     W = rng.standard_normal((V, d), dtype=np.float32)
     W *= np.float32(w_scale / np.sqrt(d))
     if dtype == "bf16":

@@ -19,8 +19,10 @@ TOL = {
     "bf16": dict(loss=2e-3, grad=1e-2, stat=1e-4),
     "fp32": dict(loss=2e-3, grad=1e-5, stat=2e-5),
 }
-# top-1/top-2 logit gap below which "bit-exact argmax" is not well-posed under fp32 accumulation
-GAP_GUARD = 1e-4
+# top-1/top-2 logit gap below which "bit-exact argmax" is not well-posed: fp32 accumulation of
+# d <= 4096 bf16 products with |z| <= ~25 differs between summation orders by ~sqrt(d) * 2^-24 * |z|
+# ~ 1e-4; rows closer than 10x that are re-drawn (the count is reported, a handful per 10^4 rows).
+GAP_GUARD = 1e-3
 
 
 class Problem:
@@ -33,18 +35,28 @@ def build_problem(B, K, d, V, dtype, seed, p_agree=0.6, fallback="uniform", ragg
     are too close for an exact argmax comparison (reports how often in `regenerated`)."""
     T = B * K
     p = Problem()
-    attempt = 0
-    while True:
-        head = synth.make_head(seed + 1000 * attempt, T, d, V, dtype)
+    if stats is not None:                      # stored oracle statistics (full-size workloads)
+        attempts = np.asarray(stats["row_attempts"])
+        head = synth.make_head(seed, T, d, V, dtype, row_attempts=attempts)
         W64 = head.W.astype(np.float64)
-        st = stats if (stats is not None and attempt == 0) else \
-            O.head_stats(head.H, None, np.zeros(T, dtype=np.int64), W64=W64)
-        near = st["gap"] < GAP_GUARD * np.maximum(1.0, np.abs(st["m"]))
-        if not near.any():
-            break
-        attempt += 1
-        assert attempt < 5
-    p.regenerated = attempt
+        st = stats
+    else:
+        attempts = np.zeros(T, dtype=np.int64)
+        head = synth.make_head(seed, T, d, V, dtype)
+        W64 = head.W.astype(np.float64)
+        st = O.head_stats(head.H, None, np.zeros(T, dtype=np.int64), W64=W64)
+        for _ in range(8):
+            near = np.nonzero(st["gap"] < GAP_GUARD)[0]
+            if len(near) == 0:
+                break
+            attempts[near] += 1
+            head = synth.make_head(seed, T, d, V, dtype, row_attempts=attempts)
+            sub = O.head_stats(head.H[near], None, np.zeros(len(near), dtype=np.int64), W64=W64)
+            for k in ("m", "lse", "gap", "argmax"):
+                st[k][near] = sub[k]
+        assert not (st["gap"] < GAP_GUARD).any()
+    p.regenerated = int((attempts > 0).sum())
+    p.row_attempts = attempts
     p.head, p.W64 = head, W64
     y, agree = synth.make_targets(seed, st["argmax"], B, K, V, p_agree, fallback)
     p.valid_len = None
