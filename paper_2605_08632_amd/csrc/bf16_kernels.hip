@@ -1,6 +1,6 @@
 // bf16 kernels of the CAT loss on gfx950: the vocabulary-head sweep with online
 // log-softmax statistics (forward), and the split-V backward (recompute + dZ, dH, dW).
-// All four contractions run on the matrix cores through gemm_nt_mainloop.
+// All four contractions run on the matrix cores through GemmNT (gemm_nt_mfma.hpp).
 #include "gemm_nt_mfma.hpp"
 #include "kernels.h"
 
@@ -12,7 +12,7 @@ static constexpr float L2E = 1.4426950408889634f;
 
 // Tile shape used by every bf16 contraction here.
 #ifndef PARD2_TILE
-#define PARD2_TILE 256, 256, 64, 4, 2
+#define PARD2_TILE 256, 256, 2, 4
 #endif
 using Cfg = TileCfg<PARD2_TILE>;
 
@@ -61,11 +61,17 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
     yt[ni] = (t < T) ? y[t] : -1;
   }
 
+  GemmNT<C> gemm(W, ldW, vt_begin * C::BM, V, H, ldH, n0, T, d, smem);
+  gemm.prefetch();
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int m0 = vt * C::BM;
     f32x16 acc[C::MI][C::NI];
     zero_acc<C>(acc);
-    gemm_nt_mainloop<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem, acc);
+    gemm.run(acc, true);
+    if (vt + 1 < vt_end) {   // the next tile's first loads fly under this tile's epilogue
+      gemm = GemmNT<C>(W, ldW, m0 + C::BM, V, H, ldH, n0, T, d, smem);
+      gemm.prefetch();
+    }
 
     const int vw0 = m0 + wp.m_of(0, 0);            // lowest vocabulary id this lane holds in the tile
     const bool ragged = m0 + C::BM > V;
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  gemm_nt_mainloop<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem, acc);
+  GemmNT<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
@@ -210,7 +216,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  gemm_nt_mainloop<C>(Wt, ldWt, m0, d, dZ, ldz, n0, T, Kc, smem, acc);
+  GemmNT<C>(Wt, ldWt, m0, d, dZ, ldz, n0, T, Kc, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
@@ -253,7 +259,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  gemm_nt_mainloop<C>(Ht, ldHt, m0, d, dZt, ldzt, n0, nrows, Tp, smem, acc);
+  GemmNT<C>(Ht, ldHt, m0, d, dZt, ldzt, n0, nrows, Tp, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
