@@ -335,7 +335,7 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
   BwdPlanBf16 p{};
   const int nVt = ceil_div(V, Cfg::BM);
-  const int max_tiles = 32;  // vocabulary tiles per chunk
+  const int max_tiles = 64;   // vocabulary tiles per chunk (Vc <= 16384)
   p.nchunks = ceil_div(nVt, max_tiles);
   p.Vc = (int64_t)ceil_div(nVt, p.nchunks) * Cfg::BM;
   p.Tp = round_up(T, Cfg::BN);   // whole token tiles: rows T..Tp of dZ are written as zeros
