@@ -1,5 +1,7 @@
 // bf16 kernels of the CAT loss on gfx950: the vocabulary-head sweep with online
 // log-softmax statistics (forward), and the split-V backward (recompute + dZ, dH, dW).
+// H, W and dZ are consumed exactly as they lie in memory (k-contiguous or k-major MFMA
+// operand panels): the backward makes no transposed copies.
 // All four contractions run on the matrix cores through GemmNT (gemm_nt_mfma.hpp).
 #include "gemm_nt_mfma.hpp"
 #include "kernels.h"
@@ -61,7 +63,7 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
     yt[ni] = (t < T) ? y[t] : -1;
   }
 
-  GemmNT<C> gemm(W, ldW, vt_begin * C::BM, V, H, ldH, n0, T, d, smem);
+  GemmNT<C> gemm(W, ldW, vt_begin * C::BM, V, d, H, ldH, n0, T, d, smem);
   gemm.prefetch();
   for (int vt = vt_begin; vt < vt_end; ++vt) {
     const int m0 = vt * C::BM;
@@ -69,7 +71,7 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
     zero_acc<C>(acc);
     gemm.run(acc, true);
     if (vt + 1 < vt_end) {   // the next tile's first loads fly under this tile's epilogue
-      gemm = GemmNT<C>(W, ldW, m0 + C::BM, V, H, ldH, n0, T, d, smem);
+      gemm = GemmNT<C>(W, ldW, m0 + C::BM, V, d, H, ldH, n0, T, d, smem);
       gemm.prefetch();
     }
 
@@ -151,16 +153,21 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
 // Backward step 1 for one vocabulary chunk: recompute the logits tile and form
 //   dZ[t,v] = g_t * (exp(z[t,v] - lse_t) - 1[v = y_t])
 // (softmax-CE gradient scaled by the constant CAT weight, Eq.11 with the stop-gradient),
-// rounded to bf16 and written in both orientations, dZ[t][v] and dZt[v][t], so that the
-// two contractions that consume it are again NT-shaped.
+// rounded to bf16 and written as dZ[t][v - chunk start].  The tile goes through LDS so
+// that every global store is a full 512-byte row segment.
 // ------------------------------------------------------------------------------------
+constexpr int DZ_PITCH = 528;   // LDS bytes per staged row of 256 bf16: 16-byte aligned, rows shift by 4 banks
+template <class C>
+constexpr int dz_lds_bytes() {
+  return C::LDS_BYTES > C::BN * DZ_PITCH ? C::LDS_BYTES : C::BN * DZ_PITCH;
+}
+
 template <class C>
 __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restrict__ H, int64_t ldH,
                                                          const __bf16* __restrict__ W, int64_t ldW,
                                                          const int32_t* __restrict__ y, const float* __restrict__ lse,
                                                          const float* __restrict__ g, int T, int d, int V, int nTt,
-                                                         int vt0, int nVtc, __bf16* __restrict__ dZ, int64_t ldz,
-                                                         __bf16* __restrict__ dZt, int64_t ldzt) {
+                                                         int vt0, int nVtc, __bf16* __restrict__ dZ, int64_t ldz) {
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int tt, vtl;
@@ -169,11 +176,13 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  GemmNT<C>(W, ldW, m0, V, H, ldH, n0, T, d, smem).run(acc);
+  GemmNT<C>(W, ldW, m0, V, d, H, ldH, n0, T, d, smem).run(acc);
 
+  // registers -> LDS tile [t][v] (a lane holds 4 consecutive v of one t: 8-byte writes)
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
-    const int t = n0 + wp.n_of(ni);
+    const int tl = wp.n_of(ni);
+    const int t = n0 + tl;
     const bool row = t < T;
     const float gt = row ? g[t] : 0.f;
     const float nl = row ? -lse[t] * L2E : -INFINITY;   // rows past T: q = 0
@@ -187,27 +196,39 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int v = m0 + ml + j;
-          const float z = (v < V) ? acc[mi][ni][rq * 4 + j] : -INFINITY;
+          const float z = (v < V) ? acc[mi][ni][rq * 4 + j] : -INFINITY;   // ids past V: dZ = 0
           const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(z, L2E, nl));
-          const float dz = gt * (q - ((v == yv) ? 1.f : 0.f));
-          pk[j] = (__bf16)dz;
-          dZt[(int64_t)(c0 + ml + j) * ldzt + t] = pk[j];
+          pk[j] = (__bf16)(gt * (q - ((v == yv) ? 1.f : 0.f)));
         }
-        *reinterpret_cast<bf16x4*>(dZ + (int64_t)t * ldz + c0 + ml) = pk;
+        *reinterpret_cast<bf16x4*>(smem + tl * DZ_PITCH + ml * 2) = pk;
       }
+  }
+  __syncthreads();
+  // LDS -> global: 32 lanes x 16 bytes cover one row of the tile
+  constexpr int ROWS_PER_PASS = C::NTHREADS / 32;
+  const int chunk = threadIdx.x & 31, r0 = threadIdx.x >> 5;
+#pragma unroll 4
+  for (int r = r0; r < C::BN; r += ROWS_PER_PASS) {
+    const int t = n0 + r;
+    if (t < T) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(smem + r * DZ_PITCH + chunk * 16);
+      *reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8) = v;
+    }
   }
 }
 
 // ------------------------------------------------------------------------------------
 // Backward step 2: dH[t,i] (+)= sum_v dZ[t,v] * W[v,i] over the chunk's vocabulary ids.
-// NT form: A = Wt (rows i, contraction v), B = dZ (rows t).  fp32 running sum across
-// chunks lives in dHacc; the last chunk writes the bf16 result.
+// A = W rows of the chunk as they lie in memory (k-major: k = v, columns i), B = dZ
+// (k-contiguous rows t).  The fp32 running sum across chunks lives in dHacc; the last
+// chunk writes the bf16 result.
 // ------------------------------------------------------------------------------------
 template <class C>
-__global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restrict__ Wt, int64_t ldWt,
+__global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restrict__ Wc, int64_t ldW,
                                                          const __bf16* __restrict__ dZ, int64_t ldz, int T, int d,
-                                                         int Kc, int nIt, int nTt, float* __restrict__ dHacc,
-                                                         __bf16* __restrict__ dH, int first, int last) {
+                                                         int nvalid, int Kc, int nIt, int nTt,
+                                                         float* __restrict__ dHacc, __bf16* __restrict__ dH, int first,
+                                                         int last) {
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int it, tt;
@@ -216,7 +237,8 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  GemmNT<C>(Wt, ldWt, m0, d, dZ, ldz, n0, T, Kc, smem).run(acc);
+  // W has nvalid rows in this chunk; dZ's columns nvalid..Kc exist and are zero
+  GemmNT<C, true, false>(Wc, ldW, m0, d, nvalid, dZ, ldz, n0, T, Kc, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
@@ -243,14 +265,14 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
 
 // ------------------------------------------------------------------------------------
 // Backward step 3: dW[v,i] = sum_t dZ[t,v] * H[t,i] for the chunk's vocabulary rows
-// (complete per chunk: no accumulation across chunks).
-// NT form: A = Ht (rows i, contraction t), B = dZt (rows v).
+// (complete per chunk: no accumulation across chunks).  Both operands are read as they
+// lie in memory, k-major with k = t: A = H (columns i), B = dZ (columns v).
 // ------------------------------------------------------------------------------------
 template <class C>
-__global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restrict__ Ht, int64_t ldHt,
-                                                         const __bf16* __restrict__ dZt, int64_t ldzt, int Tp, int d,
-                                                         int nrows, int nIt, int nVtc, __bf16* __restrict__ dWc,
-                                                         int accumulate) {
+__global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restrict__ H, int64_t ldH,
+                                                         const __bf16* __restrict__ dZ, int64_t ldz, int T, int d,
+                                                         int nvalid, int Kc, int nIt, int nVtc,
+                                                         __bf16* __restrict__ dWc, int accumulate) {
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int it, vtl;
@@ -259,12 +281,12 @@ __global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restric
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  GemmNT<C>(Ht, ldHt, m0, d, dZt, ldzt, n0, nrows, Tp, smem).run(acc);
+  GemmNT<C, true, true>(H, ldH, m0, d, T, dZ, ldz, n0, Kc, T, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
     const int vr = n0 + wp.n_of(ni);
-    if (vr >= nrows) continue;
+    if (vr >= nvalid) continue;
 #pragma unroll
     for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
@@ -283,32 +305,15 @@ __global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restric
   }
 }
 
-// dst[c][r] = src[r][c] for r < R, c < Ccols; dst columns R <= r < ldd are zero-filled.
-__global__ __launch_bounds__(256) void transpose_pad_kernel(const uint16_t* __restrict__ src, int64_t lds_, int R,
-                                                            int Ccols, uint16_t* __restrict__ dst, int64_t ldd) {
-  __shared__ uint16_t tile[64][66];
-  const int r0 = blockIdx.x * 64, c0 = blockIdx.y * 64;
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  for (int j = ty; j < 64; j += 4) {
-    const int r = r0 + j, c = c0 + tx;
-    tile[j][tx] = (r < R && c < Ccols) ? src[(int64_t)r * lds_ + c] : (uint16_t)0;
-  }
-  __syncthreads();
-  for (int j = ty; j < 64; j += 4) {
-    const int c = c0 + j, r = r0 + tx;
-    if (c < Ccols && r < ldd) dst[(int64_t)c * ldd + r] = tile[tx][j];
-  }
-}
-
 // ------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------
 static int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
 
 template <class K>
-static hipError_t allow_lds(K kernel) {
+static hipError_t allow_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                             Cfg::LDS_BYTES);
+                             bytes);
 }
 
 int fwd_num_partials_bf16(int T, int V) {
@@ -323,7 +328,7 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
                                  int d, int V, StatsOut out, hipStream_t s) {
   const int nTt = ceil_div(T, Cfg::BN), nVt = ceil_div(V, Cfg::BM), ns = out.P;
   auto k = fwd_stats_kernel<Cfg>;
-  hipError_t e = allow_lds(k);
+  hipError_t e = allow_lds(k, Cfg::LDS_BYTES);
   if (e != hipSuccess) return e;
   kt_begin(KT_FWD_STATS, s);
   hipLaunchKernelGGL(k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
@@ -338,16 +343,10 @@ BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
   const int max_tiles = 64;   // vocabulary tiles per chunk (Vc <= 16384)
   p.nchunks = ceil_div(nVt, max_tiles);
   p.Vc = (int64_t)ceil_div(nVt, p.nchunks) * Cfg::BM;
-  p.Tp = round_up(T, Cfg::BN);   // whole token tiles: rows T..Tp of dZ are written as zeros
-  p.ldHt = p.Tp;
-  p.ldWt = round_up(V, Cfg::BM);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += (bytes + 255) / 256 * 256; return at; };
   p.off_g = take((size_t)T * 4);
-  p.off_Wt = take((size_t)d * p.ldWt * 2);
-  p.off_Ht = take((size_t)d * p.ldHt * 2);
-  p.off_dZ = take((size_t)p.Tp * p.Vc * 2);
-  p.off_dZt = take((size_t)p.Vc * p.Tp * 2);
+  p.off_dZ = take((size_t)T * p.Vc * 2);
   p.off_dHacc = take((size_t)T * d * 4);
   p.total = o;
   return p;
@@ -356,42 +355,33 @@ BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                            const int32_t* y, const float* lse, const float* g, int T, int d, int V, void* dH,
                            void* dW, int accumulate_dW, char* ws, hipStream_t s) {
-  __bf16* Wt = (__bf16*)(ws + p.off_Wt);
-  __bf16* Ht = (__bf16*)(ws + p.off_Ht);
   __bf16* dZ = (__bf16*)(ws + p.off_dZ);
-  __bf16* dZt = (__bf16*)(ws + p.off_dZt);
   float* dHacc = (float*)(ws + p.off_dHacc);
+  constexpr int DZ_LDS = dz_lds_bytes<Cfg>();
   hipError_t e;
-  if ((e = allow_lds(dz_kernel<Cfg>)) != hipSuccess) return e;
-  if ((e = allow_lds(dh_kernel<Cfg>)) != hipSuccess) return e;
-  if ((e = allow_lds(dw_kernel<Cfg>)) != hipSuccess) return e;
-
-  hipLaunchKernelGGL(transpose_pad_kernel, dim3(ceil_div(p.ldWt, 64), ceil_div(d, 64)), dim3(256), 0, s,
-                     (const uint16_t*)W, ldW, V, d, (uint16_t*)Wt, p.ldWt);
-  hipLaunchKernelGGL(transpose_pad_kernel, dim3(ceil_div(p.ldHt, 64), ceil_div(d, 64)), dim3(256), 0, s,
-                     (const uint16_t*)H, ldH, T, d, (uint16_t*)Ht, p.ldHt);
+  if ((e = allow_lds(dz_kernel<Cfg>, DZ_LDS)) != hipSuccess) return e;
+  if ((e = allow_lds(dh_kernel<Cfg>, Cfg::LDS_BYTES)) != hipSuccess) return e;
+  if ((e = allow_lds(dw_kernel<Cfg>, Cfg::LDS_BYTES)) != hipSuccess) return e;
 
   const int nVt = ceil_div(V, Cfg::BM), nTt = ceil_div(T, Cfg::BN), nIt = ceil_div(d, Cfg::BM);
   for (int c = 0; c < p.nchunks; ++c) {
     const int vt0 = (int)((int64_t)c * nVt / p.nchunks), vt1 = (int)((int64_t)(c + 1) * nVt / p.nchunks);
     const int nVtc = vt1 - vt0;
     const int v0 = vt0 * Cfg::BM;
-    const int Kc = nVtc * Cfg::BM;                 // padded chunk width (dZ columns written)
-    const int nrows = (V - v0 < Kc) ? V - v0 : Kc; // valid vocabulary rows in the chunk
-    // the dZ tiles of rows t in [T, Tp) are needed (zeros) by the dW contraction
-    const int nTtp = (int)(p.Tp / Cfg::BN);
+    const int Kc = nVtc * Cfg::BM;                  // padded chunk width (dZ columns written)
+    const int nvalid = (V - v0 < Kc) ? V - v0 : Kc; // vocabulary rows that exist in the chunk
     kt_begin(KT_DZ, s);
-    hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTtp * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
-                       ldH, (const __bf16*)W, ldW, y, lse, g, T, d, V, nTtp, vt0, nVtc, dZ, p.Vc, dZt, p.Tp);
+    hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
+                       (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
     kt_end(KT_DZ, s);
     kt_begin(KT_DH, s);
-    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, Wt + v0, p.ldWt,
-                       dZ, p.Vc, T, d, Kc, nIt, nTt, dHacc, (__bf16*)dH, c == 0, c == p.nchunks - 1);
+    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
+                       (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, dHacc,
+                       (__bf16*)dH, c == 0, c == p.nchunks - 1);
     kt_end(KT_DH, s);
     kt_begin(KT_DW, s);
-    hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * ceil_div(nrows, Cfg::BN)), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
-                       Ht, p.ldHt, dZt, p.Tp, (int)p.Tp, d, nrows, nIt, ceil_div(nrows, Cfg::BN),
-                       (__bf16*)dW + (int64_t)v0 * d, accumulate_dW);
+    hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
+                       ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc, (__bf16*)dW + (int64_t)v0 * d, accumulate_dW);
     kt_end(KT_DW, s);
   }
   return hipGetLastError();

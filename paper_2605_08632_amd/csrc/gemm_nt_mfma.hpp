@@ -1,26 +1,31 @@
-// bf16 "NT" contraction main loop for gfx950 (CDNA4) matrix cores.
+// bf16 contraction main loop for gfx950 (CDNA4) matrix cores.
 //
-//   acc[m][n] += sum_k A[m][k] * B[n][k]
+//   acc[m][n] += sum_k A(m,k) * B(n,k)
 //
-// Both operands are row-major with the contraction index contiguous, which is the
-// layout v_mfma_f32_32x32x16_bf16 wants in registers: lane l supplies 8 consecutive
-// k values (k = 8*(l/32) .. +7) of row l%32 of A and of row l%32 of B, so one
-// 16-byte LDS read fills an operand.  All four contractions of the CAT loss
-// (logits, their recomputation, dH and dW) are brought to this form.
+// Each operand is given in one of two memory layouts:
+//   KC  "k-contiguous": row-major [rows][k]   (rows = m for A, n for B)
+//   KM  "k-major":      row-major [k][rows]
+// v_mfma_f32_32x32x16_bf16 wants, in registers, lane l to hold 8 consecutive k values
+// (k = 8*(l/32) .. +7) of row l%32.  From a KC panel that is one 16-byte LDS read; from a
+// KM panel it is two transposing LDS reads (ds_read_b64_tr_b16, which hands every lane of
+// a 16-lane group one 16-bit column of a 4-row x 16-column block).  With both layouts on
+// offer, all four contractions of the CAT loss (logits, their recomputation, dH, dW) read
+// H, W and dZ exactly as they lie in memory: no transposed copies.
 //
 // Work split: a workgroup of WGM x WGN wavefronts (64 lanes each) owns a BM x BN
 // output tile; each wavefront owns (BM/WGM) x (BN/WGN) of it as MI x NI MFMA
 // sub-tiles of 32x32, fp32 accumulators living in registers for the whole k loop.
 //
-// Data movement: per k stage of BK = 64 the tile's A and B panels go global -> LDS
-// directly (global_load_lds_dwordx4: no staging registers, asynchronous), into one of
-// two LDS stages; the loads of stage s+1 are issued while stage s feeds the matrix
-// cores, and one workgroup barrier per stage closes the hand-over.  LDS rows are
-// 128 bytes, unpadded (a wave-level direct load fills 1 KB = 8 rows contiguously);
-// bank conflicts are avoided by storing the 16-byte chunk c of row r at position
-// c ^ ((r >> 1) & 7), which makes any 16 consecutive rows of one chunk column hit 16
-// different 16-byte bank groups.  Operand fragments are double-buffered in registers
-// across the four k steps of a stage so that LDS latency hides under MFMA issue.
+// Data movement: per k stage of BK = 64 the tile's A and B panels (32 KB each) go
+// global -> LDS directly (global_load_lds_dwordx4: no staging registers, asynchronous),
+// into one of two LDS stages; the loads of stage s+1 are issued while stage s feeds the
+// matrix cores, and one workgroup barrier per stage closes the hand-over.  A wave-level
+// direct load fills 1 KB of LDS contiguously, so panels are unpadded; bank conflicts are
+// avoided by XOR-swizzling 16-byte chunks:
+//   KC panel: 128-byte rows; chunk c of row r sits at c ^ ((r >> 1) & 7)
+//   KM panel: 512-byte rows; chunk c of row k sits at c ^ ((k & 3) << 2)
+// Operand fragments are double-buffered in registers across the four k steps of a stage
+// so that LDS latency hides under MFMA issue.
 //
 // Accumulator layout (hardware): element r (0..15) of sub-tile (mi, ni) held by
 // lane l is
@@ -40,6 +45,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
 
 template <int BM_, int BN_, int WGM_, int WGN_>
 struct TileCfg {
@@ -48,13 +54,13 @@ struct TileCfg {
   static constexpr int NTHREADS = 64 * NWAVES;
   static constexpr int WTM = BM / WGM, WTN = BN / WGN;  // wavefront tile
   static constexpr int MI = WTM / 32, NI = WTN / 32;    // 32x32 sub-tiles per wavefront
-  static constexpr int ROWB = 128;                      // LDS row: BK bf16
-  static constexpr int A_LOADS = BM / 8 / NWAVES;       // wave-level 1 KB direct loads per stage
-  static constexpr int B_LOADS = BN / 8 / NWAVES;
-  static constexpr int STAGE_BYTES = (BM + BN) * ROWB;
+  static constexpr int A_PANEL = BM * BK * 2, B_PANEL = BN * BK * 2;   // bytes per stage
+  static constexpr int A_LOADS = A_PANEL / 1024 / NWAVES;              // wave-level 1 KB direct loads
+  static constexpr int B_LOADS = B_PANEL / 1024 / NWAVES;
+  static constexpr int STAGE_BYTES = A_PANEL + B_PANEL;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+  static_assert(BM == 256 && BN == 256, "the k-major panel addressing assumes 512-byte panel rows");
   static_assert(BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0, "wave tile must be 32-aligned");
-  static_assert(BM % (8 * NWAVES) == 0 && BN % (8 * NWAVES) == 0, "loader split");
   static_assert(A_LOADS % 2 == 0 && B_LOADS % 2 == 0, "loads are issued in two halves");
   static_assert(MI >= 2 && NI >= 2, "the split MFMA schedule needs a 2x2 sub-tile grid at least");
 };
@@ -86,72 +92,148 @@ __device__ __forceinline__ void wait_all_and_barrier() {
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n s_barrier" ::: "memory");
 }
 
-// One BM x BN x Kdim contraction.  Rows beyond M / N are clamped to the last valid
-// row (their results are garbage the caller must mask); k beyond Kdim reads as zero.
-// Kdim, lda, ldb must be multiples of 8 and the bases 16-byte aligned.  m0 < M, n0 < N.
-//
-// `prefetched`: the caller already issued stage 0 of THIS tile with gemm_nt_prefetch
-// (used to overlap a tile's first loads with the previous tile's epilogue).
-// On return every wavefront has passed a barrier after its last LDS read: LDS is free.
-template <class C>
-struct GemmNT {
-  typedef __attribute__((address_space(3))) void* lds_ptr;
-  typedef const __attribute__((address_space(1))) void* glb_ptr;
+// One wave-level direct load: lane i's 16 bytes at `src` land at LDS byte address lds + 16*i
+// (lds must be wavefront-uniform; it travels in M0).  Written as inline asm on purpose: the
+// compiler's wait-count pass, when it knows of an outstanding direct load, puts a full
+// vmcnt(0) wait before every transposing LDS read, which would serialise the pipeline.  All
+// waits on these loads are explicit (wait_all_and_barrier).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"   // M0 is reserved; naming it tells the compiler it changes
+__device__ __forceinline__ void direct_load_16(const char* src, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %1\n s_nop 0\n global_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+__device__ __forceinline__ uint32_t lds_address(const char* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)p;
+}
 
-  const char* Abase;
-  const char* Bbase;
-  char* smem;
-  uint32_t aoff[C::A_LOADS], boff[C::B_LOADS];
-  int ach[C::A_LOADS], bch[C::B_LOADS];
-  int Kdim, nk, wave;
+// One operand panel: where its direct loads come from and how its MFMA fragments are read.
+//   KM = false: global [rows][k] with row stride ld; rows past `nrows` are clamped to the last one.
+//   KM = true:  global [k][rows] with row stride ld; 8-column chunks past `nrows` are clamped
+//               (nrows - r0 must be a multiple of 8).
+// Either way k >= Kdim reads as zero and the caller masks results of clamped rows.
+//   LOADS = wave-level loads per stage, NSUB = 32-row sub-tiles per wavefront, WT = wavefront
+//   tile extent, wpos = the wavefront's index along this operand's rows.
+template <bool KM, int LOADS, int NSUB, int WT, int NWAVES>
+struct Panel {
+  const char* base;      // first byte of the tile's (row r0, k 0) / (k 0, column r0)
+  int64_t kstride;       // bytes per stage of 64 k
+  int kdim;              // k extent of this operand (KC: a multiple of 8); k >= kdim reads as zero
+  uint32_t off[LOADS];   // this lane's byte offset inside a stage, per load
+  int kch[LOADS];        // KC: k chunk (0..7) the lane loads; KM: k row (0..63) the lane loads
+  uint32_t rd_base;      // this lane's fragment read offset inside the panel
+  uint32_t rd_sub[NSUB]; // KM only: swizzled column-chunk offset per sub-tile
 
-  __device__ __forceinline__ GemmNT(const __bf16* __restrict__ A, int64_t lda, int m0, int M,
-                                    const __bf16* __restrict__ B, int64_t ldb, int n0, int N, int Kdim_,
-                                    char* smem_)
-      : smem(smem_), Kdim(Kdim_) {
+  __device__ __forceinline__ void init(const __bf16* X, int64_t ld, int r0, int nrows, int kdim_, int wave,
+                                       int wpos) {
     const int lane = threadIdx.x & 63;
-    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rin = lane >> 3, cpos = lane & 7;
-    Abase = reinterpret_cast<const char*>(A + (int64_t)m0 * lda);
-    Bbase = reinterpret_cast<const char*>(B + (int64_t)n0 * ldb);
+    kdim = kdim_;
+    if constexpr (!KM) {
+      base = reinterpret_cast<const char*>(X + (int64_t)r0 * ld);
+      kstride = 128;
+      const int rin = lane >> 3, cpos = lane & 7;
 #pragma unroll
-    for (int j = 0; j < C::A_LOADS; ++j) {
-      const int row = 8 * (wave + C::NWAVES * j) + rin;
-      ach[j] = cpos ^ ((row >> 1) & 7);
-      aoff[j] = (uint32_t)((int64_t)min(row, M - 1 - m0) * lda * 2 + ach[j] * 16);
-    }
+      for (int j = 0; j < LOADS; ++j) {
+        const int row = 8 * (wave + NWAVES * j) + rin;
+        kch[j] = cpos ^ ((row >> 1) & 7);
+        off[j] = (uint32_t)((int64_t)min(row, nrows - 1 - r0) * ld * 2 + kch[j] * 16);
+      }
+      // sub-tile strides are multiples of 32 rows, so the row part of the swizzle is a lane constant
+      rd_base = (uint32_t)((wpos * WT + (lane & 31)) * 128);
+    } else {
+      base = reinterpret_cast<const char*>(X + r0);
+      kstride = 64 * ld * 2;
+      const int last = (nrows - r0) / 8 - 1;   // last valid 8-column chunk of this tile
 #pragma unroll
-    for (int j = 0; j < C::B_LOADS; ++j) {
-      const int row = 8 * (wave + C::NWAVES * j) + rin;
-      bch[j] = cpos ^ ((row >> 1) & 7);
-      boff[j] = (uint32_t)((int64_t)min(row, N - 1 - n0) * ldb * 2 + bch[j] * 16);
+      for (int j = 0; j < LOADS; ++j) {
+        const int krow = 2 * (wave + NWAVES * j) + (lane >> 5);
+        const int ch = (lane & 31) ^ ((krow & 3) << 2);
+        kch[j] = krow;
+        off[j] = (uint32_t)((int64_t)krow * ld * 2 + min(ch, last) * 16);
+      }
+      // lane j of a 16-lane group addresses row (k0 + j/4), columns 4*(j%4)..+3 of the group's
+      // 16 columns; groups 0/1 take columns 0-15 / 16-31, groups 2/3 the next 8 k
+      const int j = lane & 15, mhalf = (lane >> 4) & 1, khalf = lane >> 5;
+      rd_base = (uint32_t)((khalf * 8 + (j >> 2)) * 512 + (j & 1) * 8);
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s) {
+        const int c = (wpos * WT + s * 32) / 8 + mhalf * 2 + ((j & 3) >> 1);
+        rd_sub[s] = (uint32_t)((c ^ ((j >> 2) << 2)) * 16);
+      }
     }
-    nk = (Kdim + 63) / 64;
   }
 
-  // half h (0/1) of the direct loads of stage kt; full = every chunk lies below Kdim
-  __device__ __forceinline__ void issue_half(int kt, int h, bool full) const {
-    const int kbyte = kt * 128;
-    char* sA = smem + (kt & 1) * C::STAGE_BYTES;
-    char* sB = sA + C::BM * C::ROWB;
+  // half h (0/1) of the direct loads of stage kt into the LDS panel at `dst`
+  __device__ __forceinline__ void issue_half(int kt, int h, bool full, char* dst, int wave) const {
+    const char* src0 = base + (int64_t)kt * kstride;
     const char* z = reinterpret_cast<const char*>(g_zero16);
 #pragma unroll
-    for (int j = 0; j < C::A_LOADS / 2; ++j) {
-      const int jj = h * (C::A_LOADS / 2) + j;
-      const char* src = Abase + kbyte + aoff[jj];
-      if (!full && kt * 64 + ach[jj] * 8 >= Kdim) src = z;
-      __builtin_amdgcn_global_load_lds((glb_ptr)src, (lds_ptr)(sA + (wave + C::NWAVES * jj) * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < C::B_LOADS / 2; ++j) {
-      const int jj = h * (C::B_LOADS / 2) + j;
-      const char* src = Bbase + kbyte + boff[jj];
-      if (!full && kt * 64 + bch[jj] * 8 >= Kdim) src = z;
-      __builtin_amdgcn_global_load_lds((glb_ptr)src, (lds_ptr)(sB + (wave + C::NWAVES * jj) * 1024), 16, 0, 0);
+    for (int j = 0; j < LOADS / 2; ++j) {
+      const int jj = h * (LOADS / 2) + j;
+      const char* src = src0 + off[jj];
+      if (!full) {
+        const int k = KM ? kt * 64 + kch[jj] : kt * 64 + kch[jj] * 8;
+        if (k >= kdim) src = z;
+      }
+      direct_load_16(src, __builtin_amdgcn_readfirstlane(lds_address(dst) + (wave + NWAVES * jj) * 1024));
     }
   }
 
-  // Issue stage 0 early (LDS must be free: all wavefronts past their last read).
+  // fragments of k step kk (16 k) of the stage whose panel starts at `p`
+  __device__ __forceinline__ void read(const char* p, int kk, int koff_kc, bf16x8 (&f)[NSUB]) const {
+    if constexpr (!KM) {
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s)
+        f[s] = *reinterpret_cast<const bf16x8*>(p + rd_base + s * 32 * 128 + koff_kc);
+    } else {
+#pragma unroll
+      for (int s = 0; s < NSUB; ++s) {
+        const char* q = p + rd_base + rd_sub[s] + kk * 16 * 512;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(q));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (__attribute__((address_space(3))) s16x4*)(q + 4 * 512));
+        const __attribute__((ext_vector_type(8))) short v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        f[s] = __builtin_bit_cast(bf16x8, v);
+      }
+    }
+  }
+};
+
+// One BM x BN contraction over k < max(KA, KB), where operand A is zero for k >= KA and B
+// for k >= KB (normally KA == KB; they differ when one operand's buffer is zero-padded in k
+// and the other's simply ends).  Strides must be multiples of 8 elements, the bases 16-byte
+// aligned, m0 < M, n0 < N; for a k-contiguous operand its k extent must be a multiple of 8,
+// for a k-major operand its row extent (M - m0 or N - n0).
+//
+// prefetch(): issue stage 0 early (LDS must be free: all wavefronts past their last read);
+// run(acc, true) then skips it.  Used to overlap a tile's first loads with the previous
+// tile's epilogue.  On return from run() every wavefront has passed a barrier after its
+// last LDS read: LDS is free.
+template <class C, bool AKM = false, bool BKM = false>
+struct GemmNT {
+  Panel<AKM, C::A_LOADS, C::MI, C::WTM, C::NWAVES> pa;
+  Panel<BKM, C::B_LOADS, C::NI, C::WTN, C::NWAVES> pb;
+  char* smem;
+  int kfull, nk, wave;   // kfull: k below which both operands are plain data
+
+  __device__ __forceinline__ GemmNT(const __bf16* __restrict__ A, int64_t lda, int m0, int M, int KA,
+                                    const __bf16* __restrict__ B, int64_t ldb, int n0, int N, int KB,
+                                    char* smem_)
+      : smem(smem_) {
+    wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    pa.init(A, lda, m0, M, KA, wave, wave % C::WGM);
+    pb.init(B, ldb, n0, N, KB, wave, wave / C::WGM);
+    kfull = min(KA, KB);
+    nk = (max(KA, KB) + 63) / 64;
+  }
+
+  __device__ __forceinline__ void issue_half(int kt, int h, bool full) const {
+    char* s = smem + (kt & 1) * C::STAGE_BYTES;
+    pa.issue_half(kt, h, full, s, wave);
+    pb.issue_half(kt, h, full, s + C::A_PANEL, wave);
+  }
+
   __device__ __forceinline__ void prefetch() const {
     issue_half(0, 0, false);
     issue_half(0, 1, false);
@@ -159,23 +241,16 @@ struct GemmNT {
 
   __device__ __forceinline__ void run(f32x16 (&acc)[C::MI][C::NI], bool prefetched = false) const {
     const int lane = threadIdx.x & 63;
-    const int wm = wave % C::WGM, wn = wave / C::WGM;
-    const int swz = ((lane & 31) >> 1) & 7;   // row-dependent part of the swizzle: sub-tile strides are
-    uint32_t koff[4];                         // multiples of 32 rows, so it is a lane constant
+    const int swz = ((lane & 31) >> 1) & 7;
+    int koff[4];   // k-contiguous panels: swizzled byte offset of the lane's k chunk per k step
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) koff[kk] = (uint32_t)(((kk * 2 + (lane >> 5)) ^ swz) * 16);
-    const uint32_t a_row = (uint32_t)((wm * C::WTM + (lane & 31)) * C::ROWB);
-    const uint32_t b_row = (uint32_t)(C::BM * C::ROWB + (wn * C::WTN + (lane & 31)) * C::ROWB);
+    for (int kk = 0; kk < 4; ++kk) koff[kk] = ((kk * 2 + (lane >> 5)) ^ swz) * 16;
 
     bf16x8 fa0[C::MI], fb0[C::NI], fa1[C::MI], fb1[C::NI];
     auto read_frags = [&](int kt, int kk, bf16x8 (&fa)[C::MI], bf16x8 (&fb)[C::NI]) {
       const char* s = smem + (kt & 1) * C::STAGE_BYTES;
-#pragma unroll
-      for (int mi = 0; mi < C::MI; ++mi)
-        fa[mi] = *reinterpret_cast<const bf16x8*>(s + a_row + mi * 32 * C::ROWB + koff[kk]);
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-        fb[ni] = *reinterpret_cast<const bf16x8*>(s + b_row + ni * 32 * C::ROWB + koff[kk]);
+      pa.read(s, kk, koff[kk], fa);
+      pb.read(s + C::A_PANEL, kk, koff[kk], fb);
     };
     // MFMAs number lo..hi-1 of the MI x NI grid (row-major numbering)
     auto mma_sel = [&](bf16x8 (&fa)[C::MI], bf16x8 (&fb)[C::NI], int lo, int hi) {
@@ -216,12 +291,12 @@ struct GemmNT {
     read_frags(0, 0, fa0, fb0);
 
     int kt = 0;
-    for (; kt < nk - 2; ++kt) {
+    const int nfull = kfull / 64;   // stages 0 .. nfull-1 need no k checks
+    for (; kt + 1 < nfull; ++kt) {
       PARD2_STAGE(issue_half(kt + 1, 0, true), issue_half(kt + 1, 1, true), true)
     }
-    if (kt < nk - 1) {   // the last stage may be partial in k
+    for (; kt < nk - 1; ++kt) {     // the last stage(s) may be partial in k
       PARD2_STAGE(issue_half(kt + 1, 0, false), issue_half(kt + 1, 1, false), true)
-      ++kt;
     }
     {
       PARD2_STAGE((void)0, (void)0, false)

@@ -64,9 +64,9 @@ hipError_t launch_row_scale(const float* w, const int32_t* y, const int32_t* val
 
 // ---- backward, bf16 storage
 struct BwdPlanBf16 {
-  int64_t ldWt, ldHt, Tp, Vc;   // padded strides / chunk width (elements)
+  int64_t Vc;          // chunk width in vocabulary ids = row stride of the dZ scratch (elements)
   int nchunks;
-  size_t off_g, off_Wt, off_Ht, off_dZ, off_dZt, off_dHacc, total;
+  size_t off_g, off_dZ, off_dHacc, total;
 };
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V);
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
