@@ -75,6 +75,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2_llama1b_bf16")
     ap.add_argument("--cpu-blocks", type=int, default=384, help="draft blocks in the oracle timing sample (0 = skip)")
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="after the timed region, run one plain device copy of this many MiB (a kernel of known "
+                         "HBM traffic for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -109,6 +112,14 @@ def main():
     ms = e0.elapsed_time(e1) / args.steps
     per_kernel = [b.pard2_cat_kernel_timing_read(k) for k in range(4)]
     b.pard2_cat_kernel_timing(False)
+
+    if args.calib_copy_mib > 0:
+        src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                       # reads and writes calib_copy_mib MiB each
+        torch.cuda.synchronize()
+        del src, dst
 
     n_valid = int((y >= 0).sum().item())
     flops_model = 6.0 * n_valid * wl.V * wl.d
