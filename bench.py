@@ -22,6 +22,20 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 
+# HBM-side bytes per launch (fetch, write) from the two rocprofv3 --pmc passes summarised in
+# profiles/c2_llama1b_hbm_traffic.md (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after the copy
+# calibration described there).  Counters cannot be read from inside this process: the figures
+# are those of the committed profile and apply to the headline workload only.
+MIB = float(1 << 20)
+MEASURED_TRAFFIC = {
+    "c2_llama1b_bf16": {
+        "fwd_stats_kernel": (6775.8 * MIB, 2.5 * MIB),
+        "dz_kernel": (838.4 * MIB, 250.5 * MIB),
+        "dh_kernel": (808.0 * MIB, 70.4 * MIB),
+        "dw_kernel": (824.4 * MIB, 63.8 * MIB),
+    },
+}
+
 
 def make_inputs(wl, device):
     """Synthetic H, W of the workload's shape, drawn on the device; targets follow the
@@ -129,6 +143,10 @@ def main():
     k_ms, k_n = per_kernel[k]
     flops_kernel_per_launch = 2.0 * wl.T * wl.V * wl.d * args.steps / max(k_n, 1)
     achieved = flops_kernel_per_launch / (k_ms / max(k_n, 1) * 1e-3) / 1e12
+    tr = MEASURED_TRAFFIC.get(wl.name, {}).get(b.KERNEL_NAMES[k])
+    traffic = None if tr is None else tr[0] + tr[1]           # bytes per launch
+    traffic_detail = None if tr is None else {"fetch_bytes": tr[0], "write_bytes": tr[1],
+                                              "source": "profiles/c2_llama1b_hbm_traffic.md"}
     res = {
         "metric": "CAT loss fwd+bwd tokens/s and % bf16 MFMA peak, d=2048 V=128256 T=8192",
         "value": n_valid / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -142,7 +160,9 @@ def main():
         "kernel_ms_per_step": {b.KERNEL_NAMES[i]: per_kernel[i][0] / args.steps for i in range(4)},
         "roofline": {"bound": "mfma", "kernel": b.KERNEL_NAMES[k], "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                     "avg_launch_ms": k_ms / max(k_n, 1), "launches": k_n, "traffic": None},
+                     "avg_launch_ms": k_ms / max(k_n, 1), "launches": k_n,
+                     "flop_per_launch": flops_kernel_per_launch, "traffic": traffic,
+                     "traffic_detail": traffic_detail},
     }
     if args.cpu_blocks > 0:
         res["cpu_baseline"] = cpu_baseline(wl, H, W, y, min(args.cpu_blocks, wl.B))
