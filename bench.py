@@ -82,8 +82,42 @@ def cpu_baseline(wl, H, W, y, n_blocks):
                       f"full V={wl.V}, d={wl.d}; {dt:.1f} s"}
 
 
+def measured_context(wl, H, W):
+    """Context for the roofline fraction, measured on the same device (not part of the timed path):
+    what the matrix cores sustain with register-resident operands (constant and random data), and
+    what the vendor GEMM library reaches on the forward-shaped contraction with the same H, W."""
+    import subprocess
+    import torch
+    ctx = {}
+    tool = os.path.join(ROOT, "paper_2605_08632_amd", "mfma_peak")
+    if os.path.exists(tool):
+        r = subprocess.run([tool, "200"], capture_output=True, text=True, timeout=120)
+        for line in r.stdout.splitlines():
+            if "TFLOP/s" in line:
+                key = "mfma_only_random_tflops" if line.startswith("random") else "mfma_only_constant_tflops"
+                ctx[key] = float(line.split("ms")[1].split("TFLOP/s")[0])
+    Hs = H[:min(wl.T, 8192)]
+    for _ in range(3):
+        Z = Hs @ W.t()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        Z = Hs @ W.t()
+    e1.record()
+    torch.cuda.synchronize()
+    del Z
+    ms = e0.elapsed_time(e1) / 10
+    ctx["vendor_gemm_fwd_shape_tflops"] = 2.0 * Hs.shape[0] * wl.V * wl.d / (ms * 1e-3) / 1e12
+    ctx["note"] = ("vendor_gemm = torch.matmul (hipBLASLt) H @ W^T materialising the logits; "
+                   "mfma_only = register-resident MFMA loop, no memory traffic")
+    return ctx
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--context", action="store_true",
+                    help="also measure the MFMA-only peak and the vendor GEMM on this device (adds ~5 s)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
@@ -164,6 +198,8 @@ def main():
                      "flop_per_launch": flops_kernel_per_launch, "traffic": traffic,
                      "traffic_detail": traffic_detail},
     }
+    if args.context:
+        res["context"] = measured_context(wl, H, W)
     if args.cpu_blocks > 0:
         res["cpu_baseline"] = cpu_baseline(wl, H, W, y, min(args.cpu_blocks, wl.B))
     print(json.dumps(res))

@@ -45,6 +45,14 @@ def build(extra_flags=(), verbose=True) -> str:
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print(f"built {LIB}")
+    # measurement aid: register-resident MFMA loop (what the matrix cores sustain without data movement)
+    tool = os.path.join(PKG, "mfma_peak")
+    r = subprocess.run([HIPCC, *FLAGS, os.path.join(CSRC, "mfma_peak.hip"), "-o", tool],
+                       capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed for mfma_peak.hip:\n" + r.stderr)
+    if verbose:
+        print(f"built {tool}")
     return LIB
 
 
