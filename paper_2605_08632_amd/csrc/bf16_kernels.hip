@@ -178,7 +178,12 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
   zero_acc<C>(acc);
   GemmNT<C>(W, ldW, m0, V, d, H, ldH, n0, T, d, smem).run(acc);
 
-  // registers -> LDS tile [t][v] (a lane holds 4 consecutive v of one t: 8-byte writes)
+  // registers -> LDS tile [t][v] (a lane holds 4 consecutive v of one t: 8-byte writes).
+  // g_t is folded into the exponent, g_t * exp(z - lse_t) = 2^(z*log2e - lse_t*log2e + log2 g_t):
+  // one FMA, one v_exp and half a convert per logit.  The single (t, y_t) element of each row
+  // is patched afterwards by the lane that holds it; vocabulary ids past V are masked only in
+  // the ragged last tile, and a negative g (negative upstream gradient) takes the plain path.
+  const bool ragged = m0 + C::BM > V;
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
     const int tl = wp.n_of(ni);
@@ -187,21 +192,49 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
     const float gt = row ? g[t] : 0.f;
     const float nl = row ? -lse[t] * L2E : -INFINITY;   // rows past T: q = 0
     const int yv = row ? y[t] : -1;
+    if (ragged) {
 #pragma unroll
-    for (int mi = 0; mi < C::MI; ++mi)
+      for (int mi = 0; mi < C::MI; ++mi)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int ml = wp.m_of(mi, rq * 4);           // 4 consecutive vocabulary ids from here
-        bf16x4 pk;
+        for (int r = 0; r < 16; ++r)
+          if (m0 + wp.m_of(mi, r) >= V) acc[mi][ni][r] = -INFINITY;   // ids past V: dZ = 0
+    }
+    if (__any(gt < 0.f)) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int v = m0 + ml + j;
-          const float z = (v < V) ? acc[mi][ni][rq * 4 + j] : -INFINITY;   // ids past V: dZ = 0
-          const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(z, L2E, nl));
-          pk[j] = (__bf16)(gt * (q - ((v == yv) ? 1.f : 0.f)));
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          bf16x4 pk;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            pk[j] = (__bf16)(gt * __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mi][ni][rq * 4 + j], L2E, nl)));
+          *reinterpret_cast<bf16x4*>(smem + tl * DZ_PITCH + wp.m_of(mi, rq * 4) * 2) = pk;
         }
-        *reinterpret_cast<bf16x4*>(smem + tl * DZ_PITCH + ml * 2) = pk;
-      }
+    } else {
+      const float nlg = nl + __builtin_amdgcn_logf(gt);   // v_log_f32 = log2; log2(0) = -inf gives dZ = 0
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          bf16x4 pk;
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            pk[j] = (__bf16)__builtin_amdgcn_exp2f(__builtin_fmaf(acc[mi][ni][rq * 4 + j], L2E, nlg));
+          *reinterpret_cast<bf16x4*>(smem + tl * DZ_PITCH + wp.m_of(mi, rq * 4) * 2) = pk;
+        }
+    }
+    // the target element: dZ = g (q - 1), computed in fp32 and rounded once
+    const int rel = yv - (m0 + wp.wm * C::WTM);
+    if (rel >= 0 && rel < C::WTM) {
+#pragma unroll
+      for (int mi = 0; mi < C::MI; ++mi)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          if (m0 + wp.m_of(mi, r) == yv) {
+            const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(acc[mi][ni][r], L2E, nl));
+            *reinterpret_cast<__bf16*>(smem + tl * DZ_PITCH + wp.m_of(mi, r) * 2) = (__bf16)(gt * (q - 1.f));
+          }
+    }
   }
   __syncthreads();
   // LDS -> global: 32 lanes x 16 bytes cover one row of the tile

@@ -85,10 +85,11 @@ def bf_ragged():
     return Hh.build_problem(37, 8, 200, 1000, "bf16", seed=21, ragged_frac=0.2, drop_some=True)
 
 
-@pytest.mark.parametrize("variant", ["self", "external", "uniform_sum"])
+@pytest.mark.parametrize("variant", ["self", "external", "uniform_sum", "negative_gradloss"])
 def test_bf16_ragged(bf_ragged, variant):
     kw = {"self": dict(beta=1.0), "external": dict(external=True),
-          "uniform_sum": dict(mode=O.W_UNIFORM, reduction=O.RED_SUM, beta=0.1)}[variant]
+          "uniform_sum": dict(mode=O.W_UNIFORM, reduction=O.RED_SUM, beta=0.1),
+          "negative_gradloss": dict(beta=1.0, grad_loss=-2.0)}[variant]
     _run_case(bf_ragged, **kw)
 
 
