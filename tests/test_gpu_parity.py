@@ -99,6 +99,14 @@ def test_bf16_multi_tile_k16():
     _run_case(p)
 
 
+def test_bf16_odd_extents():
+    # V and T not multiples of 8 (only d has to be, for 16-byte operand chunks); V one past a tile edge
+    p = Hh.build_problem(7, 5, 72, 1025, "bf16", seed=24, ragged_frac=0.3)
+    _run_case(p, beta=1.0)
+    p = Hh.build_problem(9, 3, 264, 511, "bf16", seed=25)
+    _run_case(p, external=True)
+
+
 def test_bf16_small_t():
     # fewer rows than one tile, d below one k step
     p = Hh.build_problem(3, 4, 32, 700, "bf16", seed=23)
