@@ -82,6 +82,11 @@ def cpu_baseline(wl, H, W, y, n_blocks):
                       f"full V={wl.V}, d={wl.d}; {dt:.1f} s"}
 
 
+def out_stats_argmax(b, desc, H, W, y):
+    """Greedy predictions of the head (stats-only forward of the HIP path)."""
+    return b.pard2_cat_fwd(desc, H, W, y, stats_only=True)["argmax"]
+
+
 def measured_context(wl, H, W):
     """Context for the roofline fraction, measured on the same device (not part of the timed path):
     what the matrix cores sustain with register-resident operands (constant and random data), and
@@ -118,6 +123,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--context", action="store_true",
                     help="also measure the MFMA-only peak and the vendor GEMM on this device (adds ~5 s)")
+    ap.add_argument("--variant", default="cat",
+                    help="cat (default) | decay0.8 | uniform | external | accumulate | fwd | stats")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
@@ -142,9 +149,31 @@ def main():
     dH = torch.empty(wl.T, wl.d, dtype=torch.bfloat16, device=dev)
     dW = torch.empty(wl.V, wl.d, dtype=torch.bfloat16, device=dev)
 
+    # comparators and partial passes (the default, "cat", is the headline path)
+    conf_in, accumulate, passes = None, False, "fwd+bwd"
+    if args.variant == "decay0.8":           # fixed position decay gamma^k (the ablation's comparator)
+        desc.weight_mode, desc.gamma = b.PARD2_W_DECAY, 0.8
+    elif args.variant == "uniform":          # plain PARD cross-entropy (Eq.5)
+        desc.weight_mode = b.PARD2_W_UNIFORM
+    elif args.variant == "external":         # teacher confidences supplied (the paper-exact path)
+        agree = (out_stats_argmax(b, desc, H, W, y) == y).cpu().numpy()
+        conf_in = torch.from_numpy(synth.make_external_conf(wl.seed, agree)).to(dev)
+    elif args.variant == "accumulate":       # dW += (gradient accumulation)
+        accumulate = True
+        dW.zero_()
+    elif args.variant == "fwd":
+        passes = "fwd"
+    elif args.variant == "stats":            # stats-only forward = the teacher-confidence producer
+        passes = "stats"
+    elif args.variant != "cat":
+        sys.exit(f"unknown variant {args.variant}")
+
     def step():
-        o = b.pard2_cat_fwd(desc, H, W, y, valid_len=vl, workspace=ws, out=out)
-        b.pard2_cat_bwd(desc, H, W, y, o["lse"], o["w"], valid_len=vl, dH=dH, dW=dW, workspace=ws)
+        o = b.pard2_cat_fwd(desc, H, W, y, conf_in=conf_in, valid_len=vl, workspace=ws, out=out,
+                            stats_only=(passes == "stats"))
+        if passes == "fwd+bwd":
+            b.pard2_cat_bwd(desc, H, W, y, o["lse"], o["w"], valid_len=vl, dH=dH, dW=dW, workspace=ws,
+                            accumulate_dW=accumulate)
 
     for _ in range(args.warmup):
         step()
@@ -170,7 +199,10 @@ def main():
         del src, dst
 
     n_valid = int((y >= 0).sum().item())
-    flops_model = 6.0 * n_valid * wl.V * wl.d
+    bwd = passes == "fwd+bwd"
+    flops_model = (6.0 if bwd else 2.0) * n_valid * wl.V * wl.d
+    if not bwd:
+        n_valid = wl.T                       # a forward sweep produces statistics for every row
     # dominant kernel = largest share of the step; all four run 2*T*V*d flops per step in total
     tot = [p[0] for p in per_kernel]
     k = int(np.argmax(tot))
@@ -187,10 +219,10 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={wl.T} ({wl.B} blocks x K={wl.K}), d={wl.d}, V={wl.V}, "
-                               f"CAT self-teacher, beta={wl.beta}, fwd+bwd"},
+                               f"variant {args.variant}, beta={wl.beta}, {passes}"},
         "model_tflops": flops_model / (ms * 1e-3) / 1e12,
         "pct_bf16_mfma_peak_model_flops": 100.0 * flops_model / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "executed_tflops": 8.0 * wl.T * wl.V * wl.d / (ms * 1e-3) / 1e12,
+        "executed_tflops": (8.0 if bwd else 2.0) * wl.T * wl.V * wl.d / (ms * 1e-3) / 1e12,
         "kernel_ms_per_step": {b.KERNEL_NAMES[i]: per_kernel[i][0] / args.steps for i in range(4)},
         "roofline": {"bound": "mfma", "kernel": b.KERNEL_NAMES[k], "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
@@ -200,7 +232,7 @@ def main():
     }
     if args.context:
         res["context"] = measured_context(wl, H, W)
-    if args.cpu_blocks > 0:
+    if args.cpu_blocks > 0 and args.variant == "cat":
         res["cpu_baseline"] = cpu_baseline(wl, H, W, y, min(args.cpu_blocks, wl.B))
     print(json.dumps(res))
 
