@@ -96,6 +96,25 @@ int pard2_cat_abi_version(void);
 int pard2_cat_weights(const pard2_cat_desc* desc, const float* conf, const int32_t* y,
                       const int32_t* valid_len, float* w, float* exp_len, void* stream);
 
+/* CAT weights gathered from ONE teacher pass over whole sequences (Sec.3.3: the weight of the
+ * future token x_{n+k} given the prefix x_{<=n} depends on the anchor n as well as on k):
+ *     conf[b,k] = c_seq[anchor_pos[b] + k],   s[b,k] = prod_{j<k} conf[b,j]      (Eq.10 per anchor)
+ * so overlapping draft blocks of a sequence share the teacher's per-position confidences.
+ *   c_seq      [n_pos] teacher probability of the token at each position of the concatenated
+ *                      sequences (Eq.9, teacher-forced; e.g. exp(logp_y) of a stats-only forward).
+ *   anchor_pos [B]     position of block b's slot-0 target token; negative = block absent.
+ *   seq_end    [B]     one past the last position of the sequence holding block b: slots with
+ *                      anchor_pos[b] + k >= min(seq_end[b], n_pos) do not exist (Eq.12 sums the
+ *                      anchors n <= N - k only); they get w = 0 and conf = 1.
+ *   y          [T]     or NULL, as in pard2_cat_weights.
+ *   w          [T]     out.   conf [T] out or NULL (feed it to pard2_cat_fwd as conf_in).
+ *   valid_len  [B]     out or NULL: existing slots per block (feed it to pard2_cat_fwd / _bwd).
+ *   exp_len    [B]     out or NULL.
+ */
+int pard2_cat_weights_seq(const pard2_cat_desc* desc, const float* c_seq, int64_t n_pos,
+                          const int32_t* anchor_pos, const int32_t* seq_end, const int32_t* y,
+                          float* w, float* conf, int32_t* valid_len, float* exp_len, void* stream);
+
 /* Forward: fused head contraction + online log-softmax + confidence + CAT weight + loss.
  *   H, W      storage type desc->dtype.
  *   y         [T]  int32 target ids.

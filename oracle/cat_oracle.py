@@ -139,6 +139,36 @@ def cat_weights(conf, B, K, valid_len=None, mode=W_CAT, gamma=1.0):
     return s.reshape(B * K), exp_len
 
 
+def cat_weights_seq(c_seq, anchor_pos, seq_end, K):
+    """Anchor-dependent weights of Sec.3.3 from per-position teacher confidences.
+
+    For block b anchored at position n = anchor_pos[b] of a sequence ending (exclusively) at
+    seq_end[b]:  conf[b,k] = c_seq[n + k] and  s[b,k] = prod_{j<k} c_seq[n + j]  (Eq.10 with the
+    anchor made explicit), for the slots that exist, n + k < seq_end[b] (Eq.12 sums, for offset k,
+    the anchors n <= N - k only).  Non-existing slots get conf = 1 and are excluded by valid_len.
+    Returns (conf[B*K], valid_len[B], s[B*K], exp_len[B]).
+    """
+    c_seq = np.asarray(c_seq, dtype=np.float64)
+    anchor_pos = np.asarray(anchor_pos, dtype=np.int64)
+    seq_end = np.asarray(seq_end, dtype=np.int64)
+    B = len(anchor_pos)
+    conf = np.ones((B, K))
+    s = np.ones((B, K))
+    vl = np.zeros(B, dtype=np.int64)
+    exp_len = np.zeros(B)
+    for b in range(B):
+        n = anchor_pos[b]
+        end = min(seq_end[b], len(c_seq))
+        vl[b] = 0 if n < 0 else max(0, min(K, end - n))
+        for k in range(K):
+            if k < vl[b]:
+                conf[b, k] = c_seq[n + k]
+            s[b, k] = np.prod(conf[b, :k])          # the definition: product over j < k
+            if k < vl[b]:
+                exp_len[b] += s[b, k] * conf[b, k]
+    return conf.reshape(B * K), vl, s.reshape(B * K), exp_len
+
+
 def valid_mask(y, B, K, valid_len=None, ignore_index=-100):
     """Boolean [T]: slot lies below its block's valid length and has a real target."""
     y = np.asarray(y).reshape(B, K)

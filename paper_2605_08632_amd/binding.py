@@ -18,7 +18,8 @@ PARD2_RED_MEAN_VALID, PARD2_RED_SUM = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat.so")
 EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
-           "pard2_cat_weights", "pard2_cat_fwd", "pard2_cat_bwd", "pard2_cat_kernel_timing",
+           "pard2_cat_weights", "pard2_cat_weights_seq", "pard2_cat_fwd", "pard2_cat_bwd",
+           "pard2_cat_kernel_timing",
            "pard2_cat_kernel_timing_read")
 KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel")
 
@@ -56,6 +57,8 @@ def lib() -> ctypes.CDLL:
     L.pard2_cat_abi_version.restype = ctypes.c_int
     L.pard2_cat_weights.argtypes = [D, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]
     L.pard2_cat_weights.restype = ctypes.c_int
+    L.pard2_cat_weights_seq.argtypes = [D, c_void_p, c_int64] + [c_void_p] * 8
+    L.pard2_cat_weights_seq.restype = ctypes.c_int
     L.pard2_cat_fwd.argtypes = [D] + [c_void_p] * 13 + [c_void_p, c_size_t, c_void_p]
     L.pard2_cat_fwd.restype = ctypes.c_int
     L.pard2_cat_bwd.argtypes = [D] + [c_void_p] * 9 + [c_int32, c_void_p, c_size_t, c_void_p]
@@ -159,6 +162,25 @@ def pard2_cat_weights(desc, conf, y=None, valid_len=None, w=None, exp_len=None):
                                  _stream())
     _check(rc, "pard2_cat_weights")
     return w, exp_len
+
+
+def pard2_cat_weights_seq(desc, c_seq, anchor_pos, seq_end, y=None):
+    """CAT weights gathered from per-position teacher confidences (Sec.3.3).
+    Returns (w, conf, valid_len, exp_len)."""
+    import torch
+    dev = c_seq.device
+    _check_tensor(c_seq, "c_seq", torch.float32, 1, dev)
+    _check_tensor(anchor_pos, "anchor_pos", torch.int32, desc.B, dev)
+    _check_tensor(seq_end, "seq_end", torch.int32, desc.B, dev)
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    w = torch.empty(desc.T, dtype=torch.float32, device=dev)
+    conf = torch.empty(desc.T, dtype=torch.float32, device=dev)
+    valid_len = torch.empty(desc.B, dtype=torch.int32, device=dev)
+    exp_len = torch.empty(desc.B, dtype=torch.float32, device=dev)
+    rc = lib().pard2_cat_weights_seq(ctypes.byref(desc), _ptr(c_seq), c_seq.numel(), _ptr(anchor_pos), _ptr(seq_end),
+                                     _ptr(y), _ptr(w), _ptr(conf), _ptr(valid_len), _ptr(exp_len), _stream())
+    _check(rc, "pard2_cat_weights_seq")
+    return w, conf, valid_len, exp_len
 
 
 def pard2_cat_fwd(desc, H, W, y, conf_in=None, valid_len=None, workspace=None, stats_only=False, out=None):

@@ -179,6 +179,23 @@ int pard2_cat_weights(const pard2_cat_desc* d, const float* conf, const int32_t*
   return launch_scan(a, (hipStream_t)stream) == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
 }
 
+int pard2_cat_weights_seq(const pard2_cat_desc* d, const float* conf_seq, int64_t n_pos, const int32_t* anchor_pos,
+                          const int32_t* seq_end, const int32_t* y, float* w, float* conf, int32_t* valid_len,
+                          float* exp_len, void* stream) {
+  int rc = pard2_cat_validate(d);
+  if (rc != PARD2_OK) return rc;
+  if (!conf_seq || !anchor_pos || !seq_end || !w) return PARD2_ERR_NULL;
+  if (n_pos <= 0) return PARD2_ERR_SHAPE;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  ScanArgs a{};
+  a.conf_seq = conf_seq; a.n_pos = n_pos; a.anchor_pos = anchor_pos; a.seq_end = seq_end;
+  a.conf_out = conf; a.valid_len_out = valid_len;
+  a.y = y; a.w = w; a.exp_len = exp_len;
+  a.B = d->B; a.K = d->K; a.V = d->V; a.ignore_index = d->ignore_index;
+  a.weight_mode = d->weight_mode; a.reduction = d->reduction; a.beta = d->beta; a.gamma = d->gamma;
+  return launch_scan(a, (hipStream_t)stream) == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
+}
+
 int pard2_cat_fwd(const pard2_cat_desc* d, const void* H, const void* W, const int32_t* y, const float* conf_in,
                   const int32_t* valid_len, float* loss, float* lse, float* logp_y, float* w, int32_t* argmax,
                   int32_t* accept_len, float* exp_len, int32_t* dev_status, void* workspace, size_t workspace_bytes,

@@ -41,7 +41,15 @@ hipError_t launch_combine(StatsOut st, const int32_t* y, const float* conf_in, i
 
 // Per-block exclusive prefix product (Eq.10) + masks + optional diagnostics and loss partials.
 struct ScanArgs {
-  const float* conf;        // [T]
+  const float* conf;        // [T] confidences per (block, slot), or null when gathered (below)
+  // gather mode (Sec.3.3 weights s_{n,k}): conf[b,k] = conf_seq[anchor_pos[b] + k] where that position
+  // exists (below seq_end[b] and n_pos), 1 elsewhere; the block's valid length is cut accordingly
+  const float* conf_seq;    // [n_pos] or null
+  const int32_t* anchor_pos; // [B]
+  const int32_t* seq_end;   // [B]
+  int64_t n_pos;
+  float* conf_out;          // [T] or null: the gathered confidences
+  int32_t* valid_len_out;   // [B] or null: the resulting valid lengths
   const int32_t* y;         // [T] or null
   const int32_t* valid_len; // [B] or null
   const int32_t* hit;       // [T] or null

@@ -71,12 +71,25 @@ __global__ __launch_bounds__(SCAN_THREADS) void scan_kernel(ScanArgs a) {
     const int K = a.K;
     int Kb = a.valid_len ? a.valid_len[b] : K;
     Kb = max(0, min(Kb, K));
+    int64_t pos = 0;
+    if (a.conf_seq) {   // slots whose position lies past the sequence's end do not exist (Eq.12: n <= N - k)
+      pos = a.anchor_pos[b];
+      const int64_t end = min((int64_t)a.seq_end[b], a.n_pos);
+      Kb = pos < 0 ? 0 : (int)max((int64_t)0, min((int64_t)Kb, end - pos));
+      if (a.valid_len_out) a.valid_len_out[b] = Kb;
+    }
     float run = 1.f, gpow = 1.f, el = 0.f;
     int al = 0;
     bool prefix = true;
     for (int k = 0; k < K; ++k) {
       const int64_t t = (int64_t)b * K + k;
-      const float c = a.conf[t];
+      float c;
+      if (a.conf_seq) {
+        c = k < Kb ? a.conf_seq[pos + k] : 1.f;
+        if (a.conf_out) a.conf_out[t] = c;
+      } else {
+        c = a.conf[t];
+      }
       const float s = (a.weight_mode == 0) ? run : (a.weight_mode == 1) ? gpow : 1.f;
       bool has = true;
       if (a.y) {

@@ -189,6 +189,60 @@ def test_weights_entry_point():
             assert np.all(w2[:, 0] == 1) and np.all(np.diff(w2, axis=1) <= 0) and np.all(w2 >= 0)
 
 
+def test_weights_seq_entry_point_and_teacher_pipeline():
+    """Paper-exact use: a stats-only pass over a TEACHER head gives per-position confidences
+    (Eq.9); weights_seq gathers them per anchor (Sec.3.3) with the sequence-end boundary of Eq.12;
+    the draft head's forward/backward consume the gathered confidences and valid lengths."""
+    b = _binding()
+    rng = np.random.default_rng(41)
+    K, d, V = 4, 64, 600
+    seq_lens = [9, 14, 5, 20]
+    n_pos = sum(seq_lens)
+    # teacher head over every position of the concatenated sequences
+    teacher = Hh.build_problem(n_pos, 1, d, V, "bf16", seed=42)
+    Ht, Wt, yt, _, _ = Hh.to_device(teacher)
+    tdesc = b.make_desc(n_pos, d, V, n_pos, 1, b.PARD2_BF16)
+    tout = b.pard2_cat_fwd(tdesc, Ht, Wt, yt, stats_only=True)
+    c_seq_gpu = tout["logp_y"].exp()
+    c_seq = np.exp(teacher.stats["logq"])
+    np.testing.assert_allclose(c_seq_gpu.cpu().numpy(), c_seq, rtol=2e-3, atol=1e-7)
+    # every position is an anchor; blocks near a sequence's end are cut short
+    starts = np.concatenate([[0], np.cumsum(seq_lens)[:-1]])
+    anchor_pos = np.arange(n_pos, dtype=np.int32)
+    seq_end = np.concatenate([np.full(L, s + L) for s, L in zip(starts, seq_lens)]).astype(np.int32)
+    B = n_pos
+    draft = Hh.build_problem(B, K, d, V, "bf16", seed=43)
+    # the draft's targets are the sequence's tokens: slot k of anchor n predicts position n + k
+    y = np.full((B, K), -100, dtype=np.int32)
+    for n in range(B):
+        for k in range(K):
+            if n + k < seq_end[n]:
+                y[n, k] = teacher.y[n + k]
+    draft.y = y.reshape(-1)
+    draft.stats["logq"] = O.target_logq(draft.head.H, draft.W64, draft.y, draft.stats["lse"])
+    H, W, yd, _, _ = Hh.to_device(draft)
+    desc = b.make_desc(B * K, d, V, B, K, b.PARD2_BF16, beta=0.1)
+    w, conf, vl, el = b.pard2_cat_weights_seq(desc, c_seq_gpu, torch.from_numpy(anchor_pos).cuda(),
+                                              torch.from_numpy(seq_end).cuda(), yd)
+    rconf, rvl, rs, rel = O.cat_weights_seq(c_seq, anchor_pos, seq_end, K)
+    assert np.array_equal(vl.cpu().numpy(), rvl)
+    np.testing.assert_allclose(conf.cpu().numpy(), rconf, rtol=2e-3, atol=1e-7)
+    rw = np.where(O.valid_mask(draft.y, B, K, rvl), rs, 0.0)
+    np.testing.assert_allclose(w.cpu().numpy(), rw, rtol=5e-3, atol=1e-30)
+    np.testing.assert_allclose(el.cpu().numpy(), rel, rtol=5e-3, atol=1e-6)
+    # draft forward + backward with the gathered teacher confidences
+    draft.valid_len = rvl
+    draft.conf_ext = rconf.astype(np.float32)
+    beta = float(np.float32(0.1))
+    ref = Hh.oracle_forward(draft, conf_in=draft.conf_ext, beta=beta)
+    out = b.pard2_cat_fwd(desc, H, W, yd, conf_in=torch.from_numpy(draft.conf_ext).cuda(), valid_len=vl)
+    Hh.check_forward(out, ref, draft)
+    g = O.row_scale(ref["w"], beta, ref["n_valid"])
+    rb = O.cat_backward(draft.head.H, None, draft.y, ref["lse"], g, W64=draft.W64)
+    dH, dW = b.pard2_cat_bwd(desc, H, W, yd, out["lse"], out["w"], valid_len=vl)
+    Hh.check_grads(dH, dW, rb["dH"], rb["dW"], "bf16")
+
+
 def test_accumulate_dw_and_determinism():
     p = Hh.build_problem(24, 8, 128, 900, "bf16", seed=35)
     b = _binding()

@@ -347,3 +347,39 @@ def test_target_logq_matches_head_stats():
     Z = np.einsum("ti,vi->tv", H, W)
     ok = y >= 0
     np.testing.assert_allclose(lq[ok], log_softmax(Z, axis=1)[np.arange(12)[ok], y[ok]], atol=1e-13)
+
+
+# ------------------------------------------------- anchor-dependent weights (Sec.3.3, Eq.12)
+def test_weights_seq_hand_example_and_boundary():
+    c = np.array([0.9, 0.5, 0.8, 0.25, 0.6])           # one sequence of N = 5 positions
+    K = 3
+    conf, vl, s, e = O.cat_weights_seq(c, anchor_pos=[0, 1, 2, 3, 4], seq_end=[5] * 5, K=K)
+    assert list(vl) == [3, 3, 3, 2, 1]                    # slot k exists iff n + k <= N - 1
+    np.testing.assert_allclose(s.reshape(5, K)[0], [1, 0.9, 0.45], atol=1e-15)
+    np.testing.assert_allclose(s.reshape(5, K)[3][:2], [1, 0.25], atol=1e-15)
+    np.testing.assert_allclose(conf.reshape(5, K)[3], [0.25, 0.6, 1.0], atol=0)
+    assert abs(e[0] - (0.9 + 0.45 + 0.36)) < 1e-15 and abs(e[4] - 0.6) < 1e-15
+    # Eq.12: for offset k the sum runs over N - k anchors
+    for k in range(K):
+        assert int((vl > k).sum()) == 5 - k
+
+
+def test_weights_seq_sliding_identity_and_token_major_equivalence():
+    rng = np.random.default_rng(17)
+    N, K = 40, 6
+    c = rng.random(N)
+    anchors = np.arange(N)
+    conf, vl, s, e = O.cat_weights_seq(c, anchors, np.full(N, N), K)
+    S = s.reshape(N, K)
+    for n in range(N - 1):
+        for k in range(1, K):
+            if n + k < N:                                  # s_{n,k} = c_n * s_{n+1,k-1}
+                assert abs(S[n, k] - c[n] * S[n + 1, k - 1]) < 1e-15
+    # same numbers as the token-major scan of Eq.10 on the gathered confidences
+    s2, e2 = O.cat_weights(conf, N, K, valid_len=vl)
+    np.testing.assert_allclose(s, s2, atol=1e-15)
+    np.testing.assert_allclose(e, e2, atol=1e-14)
+    # two sequences back to back: a block never reads across its own sequence's end
+    conf3, vl3, _, _ = O.cat_weights_seq(c, [18, 19, 20], [20, 20, 40], K)
+    assert list(vl3) == [2, 1, 6] and conf3.reshape(3, K)[0][2] == 1.0
+    assert list(O.cat_weights_seq(c, [-1, 39], [40, 40], K)[1]) == [0, 1]
