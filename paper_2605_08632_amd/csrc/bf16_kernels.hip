@@ -8,6 +8,8 @@
 
 #include <limits.h>
 
+#include <utility>
+
 namespace pard2 {
 
 static constexpr float L2E = 1.4426950408889634f;
@@ -255,23 +257,32 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
 // A = W rows of the chunk as they lie in memory (k-major: k = v, columns i), B = dZ
 // (k-contiguous rows t).  The fp32 running sum across chunks lives in dHacc; the last
 // chunk writes the bf16 result.
+// With few token rows the T x d output has fewer tiles than the chip has compute units;
+// then the chunk's k range is cut into `kslices` slices of Ks ids, each workgroup writes
+// its slice's partial tile to dHpart[slice] and dh_reduce_kernel adds the slices in a
+// fixed order (no atomics: reproducible).
 // ------------------------------------------------------------------------------------
 template <class C>
 __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restrict__ Wc, int64_t ldW,
                                                          const __bf16* __restrict__ dZ, int64_t ldz, int T, int d,
-                                                         int nvalid, int Kc, int nIt, int nTt,
-                                                         float* __restrict__ dHacc, __bf16* __restrict__ dH, int first,
-                                                         int last) {
+                                                         int nvalid, int Kc, int nIt, int nTt, int kslices, int Ks,
+                                                         float* __restrict__ dHacc, float* __restrict__ dHpart,
+                                                         __bf16* __restrict__ dH, int first, int last) {
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
+  const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
+  const int ntiles = nIt * nTt;
+  const int slice = id / ntiles;
   int it, tt;
-  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nIt, nTt, 8, it, tt);
+  banded_tile(id - slice * ntiles, nIt, nTt, 8, it, tt);
   const int m0 = it * C::BM, n0 = tt * C::BN;
+  const int k0 = slice * Ks;
+  const int KB = min(Ks, Kc - k0);               // dZ's columns up to Kc exist (zero past nvalid)
+  const int KA = max(0, min(KB, nvalid - k0));   // W has nvalid rows in this chunk
 
   f32x16 acc[C::MI][C::NI];
   zero_acc<C>(acc);
-  // W has nvalid rows in this chunk; dZ's columns nvalid..Kc exist and are zero
-  GemmNT<C, true, false>(Wc, ldW, m0, d, nvalid, dZ, ldz, n0, T, Kc, smem).run(acc);
+  GemmNT<C, true, false>(Wc + (int64_t)k0 * ldW, ldW, m0, d, KA, dZ + k0, ldz, n0, T, KB, smem).run(acc);
 
 #pragma unroll
   for (int ni = 0; ni < C::NI; ++ni) {
@@ -284,6 +295,10 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
         const int i = m0 + wp.m_of(mi, rq * 4);
         if (i >= d) continue;
         f32x4 v = {acc[mi][ni][rq * 4], acc[mi][ni][rq * 4 + 1], acc[mi][ni][rq * 4 + 2], acc[mi][ni][rq * 4 + 3]};
+        if (kslices > 1) {
+          *reinterpret_cast<f32x4*>(dHpart + ((int64_t)slice * T + t) * d + i) = v;
+          continue;
+        }
         f32x4* p = reinterpret_cast<f32x4*>(dHacc + (int64_t)t * d + i);
         if (!first) v += *p;
         if (last) {
@@ -293,6 +308,24 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
           *p = v;
         }
       }
+  }
+}
+
+// dHacc (+)= sum over slices of dHpart, in slice order; the last chunk writes bf16 dH instead.
+// n4 = T*d/4 groups of four floats (d is a multiple of 8).
+__global__ __launch_bounds__(256) void dh_reduce_kernel(const float* __restrict__ dHpart, int kslices, int64_t n4,
+                                                        float* __restrict__ dHacc, __bf16* __restrict__ dH,
+                                                        int first, int last) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  f32x4 v = {0.f, 0.f, 0.f, 0.f};
+  if (!first) v = reinterpret_cast<const f32x4*>(dHacc)[i];
+  for (int s = 0; s < kslices; ++s) v += reinterpret_cast<const f32x4*>(dHpart)[(int64_t)s * n4 + i];
+  if (last) {
+    bf16x4 o = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
+    reinterpret_cast<bf16x4*>(dH)[i] = o;
+  } else {
+    reinterpret_cast<f32x4*>(dHacc)[i] = v;
   }
 }
 
@@ -370,6 +403,20 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
   return hipGetLastError();
 }
 
+// Slices of the dH contraction's k range for a chunk of Kc ids: (count, ids per slice).  One slice
+// when the T x d output already fills the chip; otherwise enough slices for ~256 workgroups, each
+// at least 16 stages of 64 ids long.
+static std::pair<int, int> dh_k_slices(int T, int d, int Kc) {
+  const int tiles = ceil_div(T, Cfg::BN) * ceil_div(d, Cfg::BM);
+  if (tiles >= 192) return {1, Kc};
+  int want = ceil_div(256, tiles);
+  const int max_by_len = Kc / (16 * 64) > 1 ? Kc / (16 * 64) : 1;
+  want = want > max_by_len ? max_by_len : want;
+  want = want > 16 ? 16 : want;
+  const int Ks = (int)round_up(ceil_div(Kc, want), 64);
+  return {ceil_div(Kc, Ks), Ks};
+}
+
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
   BwdPlanBf16 p{};
   const int nVt = ceil_div(V, Cfg::BM);
@@ -381,6 +428,8 @@ BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
   p.off_g = take((size_t)T * 4);
   p.off_dZ = take((size_t)T * p.Vc * 2);
   p.off_dHacc = take((size_t)T * d * 4);
+  p.kslices = dh_k_slices(T, d, (int)p.Vc).first;
+  p.off_dHpart = take(p.kslices > 1 ? (size_t)p.kslices * T * d * 4 : 0);
   p.total = o;
   return p;
 }
@@ -390,6 +439,7 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
                            void* dW, int accumulate_dW, char* ws, hipStream_t s) {
   __bf16* dZ = (__bf16*)(ws + p.off_dZ);
   float* dHacc = (float*)(ws + p.off_dHacc);
+  float* dHpart = (float*)(ws + p.off_dHpart);
   constexpr int DZ_LDS = dz_lds_bytes<Cfg>();
   hipError_t e;
   if ((e = allow_lds(dz_kernel<Cfg>, DZ_LDS)) != hipSuccess) return e;
@@ -407,10 +457,21 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
                        (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
     kt_end(KT_DZ, s);
+    auto sl = dh_k_slices(T, d, Kc);
+    if (sl.first > p.kslices) {              // never more slices than the workspace was planned for
+      sl.second = (int)round_up(ceil_div(Kc, p.kslices), 64);
+      sl.first = ceil_div(Kc, sl.second);
+    }
+    const int first = c == 0, last = c == p.nchunks - 1;
     kt_begin(KT_DH, s);
-    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
-                       (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, dHacc,
-                       (__bf16*)dH, c == 0, c == p.nchunks - 1);
+    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt * sl.first), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
+                       (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, sl.first,
+                       sl.second, dHacc, dHpart, (__bf16*)dH, first, last);
+    if (sl.first > 1) {
+      const int64_t n4 = (int64_t)T * d / 4;
+      hipLaunchKernelGGL(dh_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, dHpart, sl.first, n4,
+                         dHacc, (__bf16*)dH, first, last);
+    }
     kt_end(KT_DH, s);
     kt_begin(KT_DW, s);
     hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,

@@ -74,7 +74,8 @@ hipError_t launch_row_scale(const float* w, const int32_t* y, const int32_t* val
 struct BwdPlanBf16 {
   int64_t Vc;          // chunk width in vocabulary ids = row stride of the dZ scratch (elements)
   int nchunks;
-  size_t off_g, off_dZ, off_dHacc, total;
+  int kslices;         // k slices of the dH contraction (1 unless T x d has too few tiles)
+  size_t off_g, off_dZ, off_dHacc, off_dHpart, total;
 };
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V);
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
