@@ -29,10 +29,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 matrix-core peak
 MIB = float(1 << 20)
 MEASURED_TRAFFIC = {
     "c2_llama1b_bf16": {
-        "fwd_stats_kernel": (6775.8 * MIB, 2.5 * MIB),
-        "dz_kernel": (838.4 * MIB, 250.5 * MIB),
-        "dh_kernel": (808.0 * MIB, 70.4 * MIB),
-        "dw_kernel": (824.4 * MIB, 63.8 * MIB),
+        "fwd_stats_kernel": (6080.1 * MIB, 2.3 * MIB),
+        "dz_kernel": (839.5 * MIB, 250.5 * MIB),
+        "dh_kernel": (808.0 * MIB, 69.3 * MIB),
+        "dw_kernel": (820.2 * MIB, 64.7 * MIB),
     },
 }
 
