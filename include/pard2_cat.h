@@ -151,13 +151,60 @@ int pard2_cat_bwd(const pard2_cat_desc* desc, const void* H, const void* W, cons
                   const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW,
                   void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- The full token loss of Eq.12: s_{n,k} (beta CE + KD), bf16 storage only ----------------
+ *
+ * Eq.12 adds a distillation term to the weighted cross-entropy without defining it.  The
+ * reading built here: KD_t = KL(p_t || q_t) = sum_v p_t(v) (log p_t(v) - log q_t(v)) at
+ * temperature 1, p_t = softmax of the TARGET model's head over its final hidden state for the
+ * same token (teacher-forced: the distribution whose entry at the true token is the c of Eq.9),
+ * q_t the draft's; the teacher receives no gradient.  Then
+ *   loss = (1/N) sum_t w_t (beta (-log q_t(y_t)) + KD_t),      w = stop-gradient CAT weight,
+ *   dZ[t,v] = g_t (beta (q_t(v) - 1[v = y_t]) + q_t(v) - p_t(v)),   g_t = grad_loss w_t / N.
+ * Neither head's T x V logits are ever stored: each vocabulary tile of both heads is contracted
+ * into registers side by side.
+ *
+ * The teacher (host struct, device pointers): H [T, d] hidden states gathered token-major by the
+ * caller (row t = the target model's state that predicts token t), W [V, d] its LM head, both
+ * bf16, 16-byte aligned, d and the strides multiples of 8.  d may differ from the draft's.
+ */
+typedef struct {
+  const void* H;      /* [T, d]  row stride ldH (elements) */
+  const void* W;      /* [V, d]  row stride ldW            */
+  int64_t ldH, ldW;
+  int32_t d;          /* teacher hidden width              */
+  int32_t reserved;   /* set to 0                          */
+} pard2_kd_teacher;
+
+/* Host-only: workspace for pard2_cat_kd_fwd / _bwd (0 if the arguments are invalid). */
+size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* desc, int32_t teacher_d);
+
+/* Forward of the Eq.12 token loss.  Arguments as pard2_cat_fwd, plus:
+ *   conf_in   [T]  confidences, or NULL = the teacher head's own p_t(y_t) (Eq.9 as printed;
+ *                  ignored rows use c = 1).
+ *   lse_t     [T]  out: logsumexp of the teacher's rows (needed by the backward).
+ *   kd        [T]  out or NULL: KL(p_t || q_t) per row.
+ * desc->dtype must be PARD2_BF16 (else PARD2_ERR_DTYPE); desc->beta must be >= 0. */
+int pard2_cat_kd_fwd(const pard2_cat_desc* desc, const void* H, const void* W,
+                     const pard2_kd_teacher* teacher, const int32_t* y, const float* conf_in,
+                     const int32_t* valid_len, float* loss, float* lse, float* lse_t, float* logp_y,
+                     float* kd, float* w, int32_t* argmax, int32_t* accept_len, float* exp_len,
+                     int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of pard2_cat_kd_fwd's loss into the draft's H and W (weight and teacher constant).
+ *   lse, lse_t, w  [T] as written by pard2_cat_kd_fwd.   Other arguments as pard2_cat_bwd. */
+int pard2_cat_kd_bwd(const pard2_cat_desc* desc, const void* H, const void* W,
+                     const pard2_kd_teacher* teacher, const int32_t* y, const int32_t* valid_len,
+                     const float* lse, const float* lse_t, const float* w, const float* grad_loss,
+                     void* dH, void* dW, int32_t accumulate_dW,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Measurement aid (not part of the method).  pard2_cat_kernel_timing(1) makes every later
- * launch of the four contraction kernels record a pair of HIP events on its stream;
+ * launch of the contraction kernels record a pair of HIP events on its stream;
  * pard2_cat_kernel_timing(0) switches it off; either call forgets earlier records.
  * pard2_cat_kernel_timing_read waits for the recorded launches of one kernel
- * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW) and returns their summed duration in
- * milliseconds and their count.  Host pointers.  Not thread-safe against concurrent
- * launches from other host threads. */
+ * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW, 4 two-head forward sweep, 5 two-head dZ)
+ * and returns their summed duration in milliseconds and their count.  Host pointers.  Not
+ * thread-safe against concurrent launches from other host threads. */
 int pard2_cat_kernel_timing(int enable);
 int pard2_cat_kernel_timing_read(int kernel, double* total_ms, int64_t* launches);
 

@@ -19,9 +19,10 @@ PARD2_RED_MEAN_VALID, PARD2_RED_SUM = 0, 1
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat.so")
 EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
            "pard2_cat_weights", "pard2_cat_weights_seq", "pard2_cat_fwd", "pard2_cat_bwd",
+           "pard2_cat_kd_workspace_bytes", "pard2_cat_kd_fwd", "pard2_cat_kd_bwd",
            "pard2_cat_kernel_timing",
            "pard2_cat_kernel_timing_read")
-KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel")
+KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel", "kd_stats_kernel", "kd_dz_kernel")
 
 
 class Pard2Error(RuntimeError):
@@ -33,6 +34,11 @@ class pard2_cat_desc(ctypes.Structure):
                 ("dtype", c_int32), ("weight_mode", c_int32), ("reduction", c_int32),
                 ("beta", c_float), ("gamma", c_float), ("ignore_index", c_int32), ("reserved", c_int32),
                 ("ldH", c_int64), ("ldW", c_int64)]
+
+
+class pard2_kd_teacher(ctypes.Structure):
+    _fields_ = [("H", c_void_p), ("W", c_void_p), ("ldH", c_int64), ("ldW", c_int64), ("d", c_int32),
+                ("reserved", c_int32)]
 
 
 _lib = None
@@ -63,6 +69,13 @@ def lib() -> ctypes.CDLL:
     L.pard2_cat_fwd.restype = ctypes.c_int
     L.pard2_cat_bwd.argtypes = [D] + [c_void_p] * 9 + [c_int32, c_void_p, c_size_t, c_void_p]
     L.pard2_cat_bwd.restype = ctypes.c_int
+    TE = POINTER(pard2_kd_teacher)
+    L.pard2_cat_kd_workspace_bytes.argtypes = [D, c_int32]
+    L.pard2_cat_kd_workspace_bytes.restype = c_size_t
+    L.pard2_cat_kd_fwd.argtypes = [D, c_void_p, c_void_p, TE] + [c_void_p] * 13 + [c_void_p, c_size_t, c_void_p]
+    L.pard2_cat_kd_fwd.restype = ctypes.c_int
+    L.pard2_cat_kd_bwd.argtypes = [D, c_void_p, c_void_p, TE] + [c_void_p] * 8 + [c_int32, c_void_p, c_size_t, c_void_p]
+    L.pard2_cat_kd_bwd.restype = ctypes.c_int
     L.pard2_cat_kernel_timing.argtypes = [ctypes.c_int]
     L.pard2_cat_kernel_timing.restype = ctypes.c_int
     L.pard2_cat_kernel_timing_read.argtypes = [ctypes.c_int, POINTER(ctypes.c_double), POINTER(c_int64)]
@@ -247,4 +260,93 @@ def pard2_cat_bwd(desc, H, W, y, lse, w, valid_len=None, grad_loss=None, dH=None
     rc = lib().pard2_cat_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(y), _ptr(valid_len), _ptr(lse), _ptr(w),
                              _ptr(grad_loss), _ptr(dH), _ptr(dW), 1 if accumulate_dW else 0, wp, wn, _stream())
     _check(rc, "pard2_cat_bwd")
+    return dH, dW
+
+
+# ---------------------------------------------------------------- Eq.12 token loss with the KD term
+def pard2_cat_kd_workspace_bytes(desc: pard2_cat_desc, teacher_d: int) -> int:
+    return lib().pard2_cat_kd_workspace_bytes(ctypes.byref(desc), teacher_d)
+
+
+def alloc_kd_workspace(desc: pard2_cat_desc, teacher_d: int, device):
+    import torch
+    n = pard2_cat_kd_workspace_bytes(desc, teacher_d)
+    if n == 0:
+        raise Pard2Error("pard2_cat_kd_workspace_bytes: invalid descriptor or teacher width")
+    return torch.empty(n + 256, dtype=torch.uint8, device=device)
+
+
+def _teacher(desc, Ht, Wt, dev):
+    import torch
+    _check_tensor(Ht, "H", torch.bfloat16, 0, dev)
+    _check_tensor(Wt, "W", torch.bfloat16, 0, dev)
+    if Ht.stride(-1) != 1 or Wt.stride(-1) != 1 or Ht.shape[0] != desc.T or Wt.shape[0] != desc.V or \
+            Ht.shape[1] != Wt.shape[1]:
+        raise Pard2Error("teacher H/W shapes do not match the descriptor")
+    return pard2_kd_teacher(Ht.data_ptr(), Wt.data_ptr(), Ht.stride(0), Wt.stride(0), Ht.shape[1], 0)
+
+
+def pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=None, valid_len=None, workspace=None, out=None):
+    """Forward of the weighted (beta CE + KD) loss.  Returns a dict of device tensors: loss, lse,
+    lse_t, logp_y, kd, w, argmax, accept_len, exp_len, dev_status."""
+    import torch
+    dev = H.device
+    _check_tensor(H, "H", torch.bfloat16, 0, dev)
+    _check_tensor(W, "W", torch.bfloat16, 0, dev)
+    if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
+        raise Pard2Error("H/W strides do not match the descriptor")
+    if tuple(H.shape) != (desc.T, desc.d) or tuple(W.shape) != (desc.V, desc.d):
+        raise Pard2Error("H/W shapes do not match the descriptor")
+    te = _teacher(desc, Ht, Wt, dev)
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    _check_tensor(conf_in, "conf_in", torch.float32, desc.T, dev)
+    _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
+    ws = alloc_kd_workspace(desc, te.d, dev) if workspace is None else workspace
+    o = {} if out is None else out
+    f32 = dict(dtype=torch.float32, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    for k in ("lse", "lse_t", "logp_y", "kd", "w"):
+        o.setdefault(k, torch.empty(desc.T, **f32))
+    o.setdefault("loss", torch.empty(1, **f32))
+    o.setdefault("argmax", torch.empty(desc.T, **i32))
+    o.setdefault("accept_len", torch.empty(desc.B, **i32))
+    o.setdefault("exp_len", torch.empty(desc.B, **f32))
+    o.setdefault("dev_status", torch.empty(1, **i32))
+    wp, wn = _ws_args(ws)
+    rc = lib().pard2_cat_kd_fwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(conf_in),
+                                _ptr(valid_len), _ptr(o["loss"]), _ptr(o["lse"]), _ptr(o["lse_t"]), _ptr(o["logp_y"]),
+                                _ptr(o["kd"]), _ptr(o["w"]), _ptr(o["argmax"]), _ptr(o["accept_len"]),
+                                _ptr(o["exp_len"]), _ptr(o["dev_status"]), wp, wn, _stream())
+    _check(rc, "pard2_cat_kd_fwd")
+    return o
+
+
+def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_loss=None, dH=None, dW=None,
+                     accumulate_dW=False, workspace=None):
+    """Backward of pard2_cat_kd_fwd's loss into the draft's H and W.  Returns (dH, dW)."""
+    import torch
+    dev = H.device
+    _check_tensor(H, "H", torch.bfloat16, 0, dev)
+    _check_tensor(W, "W", torch.bfloat16, 0, dev)
+    if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
+        raise Pard2Error("H/W strides do not match the descriptor")
+    te = _teacher(desc, Ht, Wt, dev)
+    _check_tensor(y, "y", torch.int32, desc.T, dev)
+    for name, t in (("lse", lse), ("lse_t", lse_t), ("w", w)):
+        _check_tensor(t, name, torch.float32, desc.T, dev)
+    _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
+    _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
+    dH = torch.empty(desc.T, desc.d, dtype=torch.bfloat16, device=dev) if dH is None else dH
+    if dW is None:
+        if accumulate_dW:
+            raise Pard2Error("accumulate_dW needs an existing dW")
+        dW = torch.empty(desc.V, desc.d, dtype=torch.bfloat16, device=dev)
+    _check_tensor(dH, "dH", torch.bfloat16, desc.T * desc.d, dev)
+    _check_tensor(dW, "dW", torch.bfloat16, desc.V * desc.d, dev)
+    ws = alloc_kd_workspace(desc, te.d, dev) if workspace is None else workspace
+    wp, wn = _ws_args(ws)
+    rc = lib().pard2_cat_kd_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(valid_len),
+                                _ptr(lse), _ptr(lse_t), _ptr(w), _ptr(grad_loss), _ptr(dH), _ptr(dW),
+                                1 if accumulate_dW else 0, wp, wn, _stream())
+    _check(rc, "pard2_cat_kd_bwd")
     return dH, dW

@@ -71,6 +71,43 @@ size_t bwd_bytes(const pard2_cat_desc* d) {
   return d->dtype == PARD2_BF16 ? plan_bwd_bf16(d->T, d->d, d->V).total : plan_bwd_f32(d->T, d->d, d->V).total;
 }
 
+// workspace of the two-head forward: both heads' partial statistics, per-row scratch
+struct KdFwdPlan {
+  int P;
+  size_t off_ms, off_idx, off_zy, off_ms_t, off_a_t, off_zy_t, off_tok, off_conf, off_hit, off_partials, total;
+};
+
+KdFwdPlan plan_kd_fwd(const pard2_cat_desc* d) {
+  KdFwdPlan p{};
+  p.P = kd_num_partials_bf16(d->T, d->V);
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
+  p.off_ms = take((size_t)d->T * p.P * sizeof(float2));
+  p.off_idx = take((size_t)d->T * p.P * sizeof(int32_t));
+  p.off_zy = take((size_t)d->T * 4);
+  p.off_ms_t = take((size_t)d->T * p.P * sizeof(float2));
+  p.off_a_t = take((size_t)d->T * p.P * sizeof(float));
+  p.off_zy_t = take((size_t)d->T * 4);
+  p.off_tok = take((size_t)d->T * 4);
+  p.off_conf = take((size_t)d->T * 4);
+  p.off_hit = take((size_t)d->T * 4);
+  p.off_partials = take((size_t)scan_num_groups(d->B) * 2 * sizeof(double));
+  p.total = o;
+  return p;
+}
+
+// descriptor + teacher checks shared by the two-head entry points (teacher pointers may be
+// left out for the host-only size query)
+int validate_kd(const pard2_cat_desc* d, int32_t dt, int64_t ldHt, int64_t ldWt) {
+  int rc = pard2_cat_validate(d);
+  if (rc != PARD2_OK) return rc;
+  if (d->dtype != PARD2_BF16) return PARD2_ERR_DTYPE;
+  if (!(d->beta >= 0.f)) return PARD2_ERR_HYPER;
+  if (dt <= 0 || (dt & 7) || ldHt < dt || ldWt < dt || (ldHt & 7) || (ldWt & 7)) return PARD2_ERR_SHAPE;
+  if (ldHt * 2 * 512 > 0x7fffffffLL || ldWt * 2 * 512 > 0x7fffffffLL) return PARD2_ERR_SHAPE;
+  return PARD2_OK;
+}
+
 int check_arch() {
   static int cached[64];  // 0 unknown, 1 ok, 2 wrong
   int dev = 0;
@@ -258,6 +295,81 @@ int pard2_cat_bwd(const pard2_cat_desc* d, const void* H, const void* W, const i
     if (e != hipSuccess) return PARD2_ERR_LAUNCH;
     e = launch_bwd_f32(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s);
   }
+  return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
+}
+
+size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* d, int32_t teacher_d) {
+  if (validate_kd(d, teacher_d, teacher_d, teacher_d) != PARD2_OK) return 0;
+  const size_t f = plan_kd_fwd(d).total, b = plan_bwd_bf16(d->T, d->d, d->V).total;
+  return f > b ? f : b;
+}
+
+int pard2_cat_kd_fwd(const pard2_cat_desc* d, const void* H, const void* W, const pard2_kd_teacher* te,
+                     const int32_t* y, const float* conf_in, const int32_t* valid_len, float* loss, float* lse,
+                     float* lse_t, float* logp_y, float* kd, float* w, int32_t* argmax, int32_t* accept_len,
+                     float* exp_len, int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!d || !te) return PARD2_ERR_NULL;
+  int rc = validate_kd(d, te->d, te->ldH, te->ldW);
+  if (rc != PARD2_OK) return rc;
+  if (!H || !W || !te->H || !te->W || !y || !lse || !lse_t || !logp_y) return PARD2_ERR_NULL;
+  if (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W)) return PARD2_ERR_SHAPE;
+  const KdFwdPlan p = plan_kd_fwd(d);
+  if ((rc = check_workspace(workspace, workspace_bytes, p.total)) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  KdStatsOut st{};
+  st.draft = StatsOut{(float2*)(ws + p.off_ms), (int32_t*)(ws + p.off_idx), (float*)(ws + p.off_zy), p.P};
+  st.ms_t = (float2*)(ws + p.off_ms_t);
+  st.a_t = (float*)(ws + p.off_a_t);
+  st.zy_t = (float*)(ws + p.off_zy_t);
+  float* tok = (float*)(ws + p.off_tok);
+  float* conf = (float*)(ws + p.off_conf);
+  int32_t* hit = (int32_t*)(ws + p.off_hit);
+  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, nullptr, d->beta};
+
+  if (dev_status) hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dev_status, 0);
+  if (launch_kd_stats_bf16(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s) != hipSuccess) return PARD2_ERR_LAUNCH;
+  if (launch_kd_combine(st, y, conf_in, d->T, d->V, d->ignore_index, d->beta, lse, lse_t, logp_y, kd, tok, argmax, conf,
+                        hit, dev_status, s) != hipSuccess)
+    return PARD2_ERR_LAUNCH;
+  if (loss || w || accept_len || exp_len) {
+    ScanArgs a{};
+    a.conf = conf; a.y = y; a.valid_len = valid_len; a.hit = hit;
+    a.logp_y = tok;   // minus the row's (beta CE + KD): the reduction sums w * (-tok), with coefficient 1
+    a.w = w; a.exp_len = exp_len; a.accept_len = accept_len; a.loss = loss;
+    a.loss_partials = (double*)(ws + p.off_partials);
+    a.B = d->B; a.K = d->K; a.V = d->V; a.ignore_index = d->ignore_index;
+    a.weight_mode = d->weight_mode; a.reduction = d->reduction; a.beta = 1.f; a.gamma = d->gamma;
+    if (launch_scan(a, s) != hipSuccess) return PARD2_ERR_LAUNCH;
+  }
+  return PARD2_OK;
+}
+
+int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, const pard2_kd_teacher* te,
+                     const int32_t* y, const int32_t* valid_len, const float* lse, const float* lse_t, const float* w,
+                     const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  if (!d || !te) return PARD2_ERR_NULL;
+  int rc = validate_kd(d, te->d, te->ldH, te->ldW);
+  if (rc != PARD2_OK) return rc;
+  if (!H || !W || !te->H || !te->W || !y || !lse || !lse_t || !w || !dH || !dW) return PARD2_ERR_NULL;
+  if (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W) || misaligned16(dH) ||
+      misaligned16(dW))
+    return PARD2_ERR_SHAPE;
+  const BwdPlanBf16 p = plan_bwd_bf16(d->T, d->d, d->V);
+  if ((rc = check_workspace(workspace, workspace_bytes, p.total)) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)workspace;
+  float* g = (float*)(ws + p.off_g);
+  // g_t = grad_loss w_t / N: beta sits inside the bracket of Eq.12
+  if (launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, 1.f, g, s) !=
+      hipSuccess)
+    return PARD2_ERR_LAUNCH;
+  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, lse_t, d->beta};
+  const hipError_t e =
+      launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
   return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
 }
 

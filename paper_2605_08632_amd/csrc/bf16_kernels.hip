@@ -5,6 +5,7 @@
 // All four contractions run on the matrix cores through GemmNT (gemm_nt_mfma.hpp).
 #include "gemm_nt_mfma.hpp"
 #include "kernels.h"
+#include "row_stats.hpp"
 
 #include <limits.h>
 
@@ -12,28 +13,11 @@
 
 namespace pard2 {
 
-static constexpr float L2E = 1.4426950408889634f;
-
 // Tile shape used by every bf16 contraction here.
 #ifndef PARD2_TILE
 #define PARD2_TILE 256, 256, 2, 4
 #endif
 using Cfg = TileCfg<PARD2_TILE>;
-
-// Running softmax statistics over a set of logits: max, sum of exp(z - max), and the
-// lowest index attaining the max.
-struct RowStat {
-  float m, s;
-  int idx;
-};
-__device__ __forceinline__ RowStat merge(RowStat a, RowStat b) {
-  RowStat o;
-  o.m = fmaxf(a.m, b.m);
-  const float ms = (o.m == -INFINITY) ? 0.f : o.m;  // both empty: keep s = 0 instead of NaN
-  o.s = a.s * __builtin_amdgcn_exp2f((a.m - ms) * L2E) + b.s * __builtin_amdgcn_exp2f((b.m - ms) * L2E);
-  o.idx = (a.m > b.m) ? a.idx : (b.m > a.m) ? b.idx : min(a.idx, b.idx);
-  return o;
-}
 
 // ------------------------------------------------------------------------------------
 // Forward sweep (head contraction of Eq.4/5 + online log-softmax of the log P in Eq.11).
@@ -436,7 +420,7 @@ BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
 
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                            const int32_t* y, const float* lse, const float* g, int T, int d, int V, void* dH,
-                           void* dW, int accumulate_dW, char* ws, hipStream_t s) {
+                           void* dW, int accumulate_dW, char* ws, hipStream_t s, const KdTeacher* kd) {
   __bf16* dZ = (__bf16*)(ws + p.off_dZ);
   float* dHacc = (float*)(ws + p.off_dHacc);
   float* dHpart = (float*)(ws + p.off_dHpart);
@@ -453,10 +437,14 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     const int v0 = vt0 * Cfg::BM;
     const int Kc = nVtc * Cfg::BM;                  // padded chunk width (dZ columns written)
     const int nvalid = (V - v0 < Kc) ? V - v0 : Kc; // vocabulary rows that exist in the chunk
-    kt_begin(KT_DZ, s);
-    hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
-                       (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
-    kt_end(KT_DZ, s);
+    if (kd) {   // distillation term present: the two-head recompute forms dZ
+      if ((e = launch_kd_dz_bf16(H, ldH, W, ldW, *kd, y, lse, g, T, d, V, v0, Kc, dZ, p.Vc, s)) != hipSuccess) return e;
+    } else {
+      kt_begin(KT_DZ, s);
+      hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
+                         (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
+      kt_end(KT_DZ, s);
+    }
     auto sl = dh_k_slices(T, d, Kc);
     if (sl.first > p.kslices) {              // never more slices than the workspace was planned for
       sl.second = (int)round_up(ceil_div(Kc, p.kslices), 64);

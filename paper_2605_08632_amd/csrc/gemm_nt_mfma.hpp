@@ -59,7 +59,6 @@ struct TileCfg {
   static constexpr int B_LOADS = B_PANEL / 1024 / NWAVES;
   static constexpr int STAGE_BYTES = A_PANEL + B_PANEL;
   static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
-  static_assert(BM == 256 && BN == 256, "the k-major panel addressing assumes 512-byte panel rows");
   static_assert(BM % (32 * WGM) == 0 && BN % (32 * WGN) == 0, "wave tile must be 32-aligned");
   static_assert(A_LOADS % 2 == 0 && B_LOADS % 2 == 0, "loads are issued in two halves");
   static_assert(MI >= 2 && NI >= 2, "the split MFMA schedule needs a 2x2 sub-tile grid at least");
@@ -212,6 +211,8 @@ struct Panel {
 // last LDS read: LDS is free.
 template <class C, bool AKM = false, bool BKM = false>
 struct GemmNT {
+  static_assert((!AKM || C::BM == 256) && (!BKM || C::BN == 256),
+                "the k-major panel addressing assumes 512-byte panel rows");
   Panel<AKM, C::A_LOADS, C::MI, C::WTM, C::NWAVES> pa;
   Panel<BKM, C::B_LOADS, C::NI, C::WTN, C::NWAVES> pb;
   char* smem;

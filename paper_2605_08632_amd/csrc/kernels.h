@@ -9,9 +9,9 @@ namespace pard2 {
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Optional per-kernel timing (off by default): when switched on through
-// pard2_cat_kernel_timing(), every launch of one of the four contraction kernels is
+// pard2_cat_kernel_timing(), every launch of one of the contraction kernels is
 // bracketed by a pair of HIP events on its stream.
-enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_COUNT = 4 };
+enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_KD_STATS = 4, KT_KD_DZ = 5, KT_COUNT = 6 };
 void kt_begin(int id, hipStream_t s);
 void kt_end(int id, hipStream_t s);
 
@@ -78,9 +78,42 @@ struct BwdPlanBf16 {
   size_t off_g, off_dZ, off_dHacc, off_dHpart, total;
 };
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V);
+// The teacher side of the distillation term (Eq.12), when present: dZ then is
+// g_t (beta (q - 1[v = y_t]) + q - p) with p the teacher head's softmax.
+struct KdTeacher {
+  const void* H;       // [T, d]
+  const void* W;       // [V, d]
+  int64_t ldH, ldW;
+  int d;
+  const float* lse;    // [T] logsumexp of the teacher's rows
+  float beta;
+};
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                            const int32_t* y, const float* lse, const float* g, int T, int d, int V,
-                           void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s);
+                           void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s,
+                           const KdTeacher* kd = nullptr);
+
+// ---- two-head (draft + teacher) kernels of the distillation term, bf16 storage
+// Forward sweep: the draft's statistics as in StatsOut plus, per row and vocabulary range, the
+// teacher's (max, sum of exp) and a = sum_v exp(zT - max) (zT - zD); zy_t = teacher logit of the target.
+struct KdStatsOut {
+  StatsOut draft;
+  float2* ms_t;
+  float* a_t;
+  float* zy_t;
+};
+int kd_num_partials_bf16(int T, int V);
+hipError_t launch_kd_stats_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& teacher,
+                                const int32_t* y, int T, int d, int V, KdStatsOut out, hipStream_t s);
+// Merge partials of both heads: lse, lse_t, log q(y), KL(p || q), argmax, confidence (given, or the
+// teacher's p(y)), hit, and tok[t] = beta log q(y) - KL (minus the row's loss term; 0 on rows without target).
+hipError_t launch_kd_combine(KdStatsOut st, const int32_t* y, const float* conf_in, int T, int V, int ignore_index,
+                             float beta, float* lse, float* lse_t, float* logp_y, float* kd, float* tok,
+                             int32_t* argmax, float* conf, int32_t* hit, int32_t* dev_status, hipStream_t s);
+// dZ of one vocabulary chunk (tiles of kd_dz_tile() ids starting at id v0, Kc ids wide) into dZ[t][v - v0].
+hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& teacher,
+                             const int32_t* y, const float* lse, const float* g, int T, int d, int V, int v0, int Kc,
+                             void* dZ, int64_t ldz, hipStream_t s);
 
 // ---- backward, fp32 storage
 struct BwdPlanF32 {

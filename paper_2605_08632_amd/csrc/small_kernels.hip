@@ -53,6 +53,67 @@ hipError_t launch_combine(StatsOut st, const int32_t* y, const float* conf_in, i
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- combine, two heads (Eq.12 with KD)
+// One thread per token row.  Draft side as above.  Teacher side: lse_t, the teacher's p_t(y_t)
+// (the confidence of Eq.9 unless one is given) and
+//   KL(p_t || q_t) = sum_v p_t(v) (zT - zD)(v) - lse_t + lse = a / s - lse_t + lse.
+// tok[t] = beta log q_t(y_t) - KL: minus the row's term beta CE + KD, in the place where the
+// CE-only path hands log q_t(y_t) to the weighted reduction.
+__global__ __launch_bounds__(256) void kd_combine_kernel(
+    const float2* __restrict__ ms, const int32_t* __restrict__ idx, const float* __restrict__ zy,
+    const float2* __restrict__ ms_t, const float* __restrict__ a_t, const float* __restrict__ zy_t, int P,
+    const int32_t* __restrict__ y, const float* __restrict__ conf_in, int T, int V, int ignore_index, float beta,
+    float* __restrict__ lse, float* __restrict__ lse_t, float* __restrict__ logp_y, float* __restrict__ kd,
+    float* __restrict__ tok, int32_t* __restrict__ argmax, float* __restrict__ conf, int32_t* __restrict__ hit,
+    int32_t* __restrict__ dev_status) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  const float2* p = ms + (int64_t)t * P;
+  const int32_t* pi = idx + (int64_t)t * P;
+  const float2* pt = ms_t + (int64_t)t * P;
+  const float* pa = a_t + (int64_t)t * P;
+  float m = -INFINITY, mt = -INFINITY;
+  int am = INT_MAX;
+  for (int j = 0; j < P; ++j) {
+    const float mj = p[j].x;
+    if (mj > m) {
+      m = mj;
+      am = pi[j];
+    }
+    mt = fmaxf(mt, pt[j].x);
+  }
+  float s = 0.f, st = 0.f, at = 0.f;
+  for (int j = 0; j < P; ++j) {
+    s += p[j].y * expf(p[j].x - m);
+    const float e = expf(pt[j].x - mt);
+    st += pt[j].y * e;
+    at += pa[j] * e;
+  }
+  const float l = m + logf(s), lt = mt + logf(st);
+  const float kl = at / st - lt + l;
+  const int yv = y[t];
+  const bool ok = yv >= 0 && yv < V;
+  if (!ok && yv != ignore_index && dev_status) *dev_status = 1;
+  const float lp = ok ? zy[t] - l : 0.f;
+  lse[t] = l;
+  lse_t[t] = lt;
+  logp_y[t] = lp;
+  if (kd) kd[t] = kl;
+  tok[t] = ok ? beta * lp - kl : 0.f;
+  if (argmax) argmax[t] = am;
+  if (conf) conf[t] = conf_in ? conf_in[t] : (ok ? expf(zy_t[t] - lt) : 1.f);
+  if (hit) hit[t] = ok && am == yv;
+}
+
+hipError_t launch_kd_combine(KdStatsOut st, const int32_t* y, const float* conf_in, int T, int V, int ignore_index,
+                             float beta, float* lse, float* lse_t, float* logp_y, float* kd, float* tok,
+                             int32_t* argmax, float* conf, int32_t* hit, int32_t* dev_status, hipStream_t s) {
+  hipLaunchKernelGGL(kd_combine_kernel, dim3((T + 255) / 256), dim3(256), 0, s, st.draft.ms, st.draft.idx, st.draft.zy,
+                     st.ms_t, st.a_t, st.zy_t, st.draft.P, y, conf_in, T, V, ignore_index, beta, lse, lse_t, logp_y,
+                     kd, tok, argmax, conf, hit, dev_status);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- per-block scan
 // One thread per draft block walks its K slots left to right:
 //   s_0 = 1, s_k = s_{k-1} * c_{k-1}   (Eq.10), or gamma^k / 1 for the comparators,
