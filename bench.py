@@ -124,7 +124,9 @@ def main():
     ap.add_argument("--context", action="store_true",
                     help="also measure the MFMA-only peak and the vendor GEMM on this device (adds ~5 s)")
     ap.add_argument("--variant", default="cat",
-                    help="cat (default) | decay0.8 | uniform | external | accumulate | fwd | stats")
+                    help="cat (default) | decay0.8 | uniform | external | accumulate | fwd | stats | "
+                         "kd (the Eq.12 token loss: beta CE + KD against a teacher head of width --teacher-d)")
+    ap.add_argument("--teacher-d", type=int, default=4096, help="hidden width of the teacher head (variant kd)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
@@ -165,10 +167,35 @@ def main():
         passes = "fwd"
     elif args.variant == "stats":            # stats-only forward = the teacher-confidence producer
         passes = "stats"
+    elif args.variant == "kd":               # weighted beta CE + KL(teacher || draft), two-head kernels
+        # teacher recipe of synth.make_teacher, drawn on the device: draft operands extended by
+        # independent columns, so that teacher logits = draft logits + noise of std ~2
+        dt = args.teacher_d
+        if dt <= wl.d or dt % 8:
+            sys.exit("--teacher-d must exceed the draft width and be a multiple of 8")
+        g = torch.Generator(device=dev)
+        g.manual_seed(wl.seed + 12)
+        E = torch.randn(wl.T, dt - wl.d, generator=g, device=dev, dtype=torch.float32)
+        E = 2.0 * E / E.pow(2).mean(dim=1, keepdim=True).sqrt()
+        Ht = torch.cat([H, E.to(torch.bfloat16)], dim=1).contiguous()
+        del E
+        Wt = torch.empty(wl.V, dt, dtype=torch.bfloat16, device=dev)
+        Wt[:, :wl.d] = W
+        Wt[:, wl.d:] = (torch.randn(wl.V, dt - wl.d, generator=g, device=dev, dtype=torch.float32)
+                        / np.sqrt(dt - wl.d)).to(torch.bfloat16)
+        ws = b.alloc_kd_workspace(desc, dt, dev)
     elif args.variant != "cat":
         sys.exit(f"unknown variant {args.variant}")
+    kd = args.variant == "kd"
+
+    def step_kd():
+        o = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws, out=out)
+        b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, o["lse"], o["lse_t"], o["w"], valid_len=vl, dH=dH, dW=dW,
+                           workspace=ws)
 
     def step():
+        if kd:
+            return step_kd()
         o = b.pard2_cat_fwd(desc, H, W, y, conf_in=conf_in, valid_len=vl, workspace=ws, out=out,
                             stats_only=(passes == "stats"))
         if passes == "fwd+bwd":
@@ -187,7 +214,7 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / args.steps
-    per_kernel = [b.pard2_cat_kernel_timing_read(k) for k in range(4)]
+    per_kernel = [b.pard2_cat_kernel_timing_read(k) for k in range(len(b.KERNEL_NAMES))]
     b.pard2_cat_kernel_timing(False)
 
     if args.calib_copy_mib > 0:
@@ -201,13 +228,19 @@ def main():
     n_valid = int((y >= 0).sum().item())
     bwd = passes == "fwd+bwd"
     flops_model = (6.0 if bwd else 2.0) * n_valid * wl.V * wl.d
+    flops_exec = (8.0 if bwd else 2.0) * wl.T * wl.V * wl.d
+    if kd:                                   # + the teacher head: once in the loss, once more in the recompute
+        flops_model += 2.0 * n_valid * wl.V * args.teacher_d
+        flops_exec += 4.0 * wl.T * wl.V * args.teacher_d
     if not bwd:
         n_valid = wl.T                       # a forward sweep produces statistics for every row
-    # dominant kernel = largest share of the step; all four run 2*T*V*d flops per step in total
+    # dominant kernel = largest share of the step; per step each single-head kernel runs 2*T*V*d flops in
+    # total, each two-head kernel 2*T*V*(d + dt)
     tot = [p[0] for p in per_kernel]
     k = int(np.argmax(tot))
     k_ms, k_n = per_kernel[k]
-    flops_kernel_per_launch = 2.0 * wl.T * wl.V * wl.d * args.steps / max(k_n, 1)
+    width = wl.d + args.teacher_d if b.KERNEL_NAMES[k].startswith("kd_") else wl.d
+    flops_kernel_per_launch = 2.0 * wl.T * wl.V * width * args.steps / max(k_n, 1)
     achieved = flops_kernel_per_launch / (k_ms / max(k_n, 1) * 1e-3) / 1e12
     tr = MEASURED_TRAFFIC.get(wl.name, {}).get(b.KERNEL_NAMES[k])
     traffic = None if tr is None else tr[0] + tr[1]           # bytes per launch
@@ -219,11 +252,12 @@ def main():
         "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{wl.name}: T={wl.T} ({wl.B} blocks x K={wl.K}), d={wl.d}, V={wl.V}, "
-                               f"variant {args.variant}, beta={wl.beta}, {passes}"},
+                               f"variant {args.variant}{f' (teacher d={args.teacher_d})' if kd else ''}, beta={wl.beta}, {passes}"},
         "model_tflops": flops_model / (ms * 1e-3) / 1e12,
         "pct_bf16_mfma_peak_model_flops": 100.0 * flops_model / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-        "executed_tflops": (8.0 if bwd else 2.0) * wl.T * wl.V * wl.d / (ms * 1e-3) / 1e12,
-        "kernel_ms_per_step": {b.KERNEL_NAMES[i]: per_kernel[i][0] / args.steps for i in range(4)},
+        "executed_tflops": flops_exec / (ms * 1e-3) / 1e12,
+        "kernel_ms_per_step": {b.KERNEL_NAMES[i]: per_kernel[i][0] / args.steps
+                               for i in range(len(b.KERNEL_NAMES)) if per_kernel[i][1] > 0},
         "roofline": {"bound": "mfma", "kernel": b.KERNEL_NAMES[k], "achieved": achieved,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                      "avg_launch_ms": k_ms / max(k_n, 1), "launches": k_n,

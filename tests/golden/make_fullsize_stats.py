@@ -6,6 +6,11 @@ parity tests at full size can compare every row without redoing the fp64 vocabul
 Calls only oracle/ and the seeded input generators; nothing here comes from the HIP path.
 
     python tests/golden/make_fullsize_stats.py [workload ...]
+    python tests/golden/make_fullsize_stats.py kd:<workload>:<teacher width>
+
+The second form writes fullsize_kd_<workload>_dt<width>.npz: the teacher head's logsumexp and
+KL(teacher || draft) of every row (both target-independent) for the two-head loss, from the
+workload's stored draft inputs plus synth.make_teacher; the draft statistics file must exist.
 
 Rows whose two largest logits nearly tie (gap < tests.helpers.GAP_GUARD) are re-drawn, each
 from its own seeded stream, until none is left; `row_attempts` records how often, and
@@ -55,5 +60,26 @@ def main(names):
               f"{time.time() - t0:.0f} s -> {out} ({os.path.getsize(out) / 1024:.0f} KiB)", flush=True)
 
 
+def main_kd(name, dt):
+    from oracle import cat_kd_oracle as KD
+    wl = synth.WORKLOADS[name]
+    t0 = time.time()
+    base = np.load(os.path.join(ROOT, "tests", "golden", f"fullsize_{name}.npz"))
+    head = synth.make_head(wl.seed, wl.T, wl.d, wl.V, wl.dtype, row_attempts=np.asarray(base["row_attempts"]))
+    teacher = synth.make_teacher(wl.seed, head, dt)
+    st = KD.kd_stats(head.H, head.W.astype(np.float64), teacher.H, teacher.W.astype(np.float64),
+                     np.zeros(wl.T, dtype=np.int64))
+    assert np.allclose(st["lse"], base["lse"], rtol=0, atol=1e-9)      # same draft inputs as the stored file
+    out = os.path.join(ROOT, "tests", "golden", f"fullsize_kd_{name}_dt{dt}.npz")
+    np.savez_compressed(out, lse_t=st["lse_t"], kd=st["kd"], teacher_d=np.int64(dt))
+    print(f"kd {name} dt={dt}: {time.time() - t0:.0f} s -> {out} ({os.path.getsize(out) / 1024:.0f} KiB)", flush=True)
+
+
 if __name__ == "__main__":
-    main(sys.argv[1:] or FULLSIZE)
+    args = sys.argv[1:]
+    for a in [a for a in args if a.startswith("kd:")]:
+        _, name, dt = a.split(":")
+        main_kd(name, int(dt))
+    plain = [a for a in args if not a.startswith("kd:")]
+    if plain or not args:
+        main(plain or FULLSIZE)

@@ -79,3 +79,74 @@ def test_fullsize_workload(name):
     rhs = (dH64 * H.double()).sum().item()
     assert abs(lhs - rhs) <= 1e-2 * max(abs(lhs), abs(rhs)), (lhs, rhs)
     print(f"[fullsize] identities ok: <dW,W> {lhs:.6e} <dH,H> {rhs:.6e}", flush=True)
+
+
+def test_fullsize_kd_c2_teacher4096():
+    """The Eq.12 token loss (beta CE + KD) at the headline shape with a teacher head of width 4096,
+    in the launch configuration `bench.py --variant kd` times.  Forward: every row against the oracle
+    (the teacher's logsumexp and KL(p || q) of every row are stored by make_fullsize_stats.py, from
+    oracle/ only).  Backward: sampled blocks / vocabulary rows one by one, plus the two identities."""
+    from oracle import cat_kd_oracle as KD
+    from paper_2605_08632_amd import binding as b
+    name, dt = "c2_llama1b_bf16", 4096
+    wl = synth.WORKLOADS[name]
+    print(f"[fullsize kd] {name}: T={wl.T} d={wl.d} dt={dt} V={wl.V}", flush=True)
+    stats = {k: v for k, v in np.load(os.path.join(GOLDEN, f"fullsize_{name}.npz")).items()}
+    stats["argmax"] = stats["argmax"].astype(np.int64)
+    gold = np.load(os.path.join(GOLDEN, f"fullsize_kd_{name}_dt{dt}.npz"))
+    assert int(gold["teacher_d"]) == dt
+    p = Hh.build_problem(wl.B, wl.K, wl.d, wl.V, "bf16", wl.seed, p_agree=wl.p_agree, fallback=wl.fallback,
+                         ragged_frac=wl.ragged_frac, stats=stats)
+    teacher = synth.make_teacher(wl.seed, p.head, dt)
+    kst = dict(p.stats)
+    kst["lse_t"], kst["kd"] = gold["lse_t"], gold["kd"]
+    kst["logp_t"] = O.target_logq(teacher.H, teacher.W, p.y, gold["lse_t"])
+    beta = float(np.float32(wl.beta))
+    ref = KD.cat_kd_forward(p.head.H, None, teacher.H, None, p.y, p.B, p.K, valid_len=p.valid_len, beta=beta,
+                            stats=kst)
+
+    H, W, y, vl, _ = Hh.to_device(p)
+    Ht = torch.from_numpy(teacher.H_bits.view(np.int16)).view(torch.bfloat16).to(H.device)
+    Wt = torch.from_numpy(teacher.W_bits.view(np.int16)).view(torch.bfloat16).to(H.device)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=wl.beta)
+    ws = b.alloc_kd_workspace(desc, dt, H.device)
+    out = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws)
+    torch.cuda.synchronize()
+    g = Hh.check_forward(out, ref, p, stats_only=True)
+    tol = Hh.TOL["bf16"]
+    np.testing.assert_allclose(g["lse_t"], ref["lse_t"], rtol=tol["stat"], atol=tol["stat"])
+    np.testing.assert_allclose(g["kd"], ref["kd"], rtol=3 * tol["stat"], atol=3 * tol["stat"])
+    np.testing.assert_allclose(g["w"], ref["w"], rtol=10 * tol["stat"], atol=1e-30)
+    assert abs(g["loss"][0] - ref["loss"]) <= tol["loss"] * abs(ref["loss"])
+    print(f"[fullsize kd] forward ok: loss {g['loss'][0]:.6f} oracle {ref['loss']:.6f}, "
+          f"mean KL {ref['kd'].mean():.4f}", flush=True)
+
+    dH, dW = b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, out["lse"], out["lse_t"], out["w"], valid_len=vl,
+                                workspace=ws)
+    torch.cuda.synchronize()
+    gr = KD.kd_row_scale(ref["w"], ref["n_valid"])
+    rng = np.random.default_rng([wl.seed, 78])
+    blocks = {0, wl.B - 1, wl.B // 2} | set(rng.integers(0, wl.B, 5).tolist())
+    rows = np.concatenate([np.arange(bk * wl.K, (bk + 1) * wl.K) for bk in sorted(blocks)])
+    ids, counts = np.unique(p.y[p.y >= 0], return_counts=True)
+    frequent = ids[np.argsort(-counts)[:96]]
+    edges = np.array([0, 127, 128, 16383, 16384, wl.V - 129, wl.V - 2, wl.V - 1])
+    vrows = np.unique(np.concatenate([frequent, edges, rng.integers(0, wl.V, 96)]))
+    rb = KD.cat_kd_backward(p.head.H, p.W64, teacher.H, teacher.W, p.y, ref["lse"], ref["lse_t"], gr, beta,
+                            slab=64, rows=rows, vrows=vrows)
+    gH = dH[torch.from_numpy(rows).to(H.device)].float().cpu().numpy()
+    gW = dW[torch.from_numpy(vrows).to(H.device)].float().cpu().numpy()
+    eH = np.max(np.abs(gH - rb["dH"])) / np.max(np.abs(rb["dH"]))
+    eW = np.max(np.abs(gW - rb["dW"])) / np.max(np.abs(rb["dW"]))
+    print(f"[fullsize kd] backward sampled: dH max-rel {eH:.2e} ({len(rows)} rows), "
+          f"dW max-rel {eW:.2e} ({len(vrows)} vocabulary rows)", flush=True)
+    assert eH <= tol["grad"] and eW <= tol["grad"]
+
+    dW64, dH64 = dW.double(), dH.double()
+    colsum = dW64.sum(dim=0).abs()
+    colabs = dW64.abs().sum(dim=0)
+    assert (colsum <= 1e-3 * colabs + 1e-30).all().item(), "columns of dW do not sum to zero"
+    lhs = (dW64 * W.double()).sum().item()
+    rhs = (dH64 * H.double()).sum().item()
+    assert abs(lhs - rhs) <= 1e-2 * max(abs(lhs), abs(rhs)), (lhs, rhs)
+    print(f"[fullsize kd] identities ok: <dW,W> {lhs:.6e} <dH,H> {rhs:.6e}", flush=True)
