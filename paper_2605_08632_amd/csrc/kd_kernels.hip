@@ -14,7 +14,10 @@
 
 namespace pard2 {
 
-using KdCfg = TileCfg<128, 256, 2, 4>;
+#ifndef PARD2_KD_TILE
+#define PARD2_KD_TILE 128, 256, 2, 4
+#endif
+using KdCfg = TileCfg<PARD2_KD_TILE>;
 
 // Teacher-side running statistics of a row over a set of ids: max, s = sum exp(zT - max) and
 // a = sum exp(zT - max) (zT - zD); at the end  sum_v p(v) (zT - zD)(v) = a / s.
@@ -210,10 +213,13 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_stats_kernel(
 // LDS tile so that every global store is a full 256-byte row segment.  A tile that lies
 // entirely past V inside the chunk's padded width writes zeros.
 // ------------------------------------------------------------------------------------
-constexpr int KD_DZ_PITCH = 272;   // LDS bytes per staged row of 128 bf16: 16-byte aligned, rows shift by 4 banks
+template <class C>
+constexpr int kd_dz_pitch() {   // LDS bytes per staged row of BM bf16: 16-byte aligned, rows shift by 4 banks
+  return C::BM * 2 + 16;
+}
 template <class C>
 constexpr int kd_dz_lds_bytes() {
-  return C::LDS_BYTES > C::BN * KD_DZ_PITCH ? C::LDS_BYTES : C::BN * KD_DZ_PITCH;
+  return C::LDS_BYTES > C::BN * kd_dz_pitch<C>() ? C::LDS_BYTES : C::BN * kd_dz_pitch<C>();
 }
 
 template <class C>
@@ -224,6 +230,7 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
     const float* __restrict__ g, float beta, int T, int d, int dt, int V, int nTt, int vt0, int nVtc,
     __bf16* __restrict__ dZ, int64_t ldz) {
   extern __shared__ __align__(16) char smem[];
+  constexpr int KD_DZ_PITCH = kd_dz_pitch<C>();
   const WavePos<C> wp;
   int tt, vtl;
   banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, 8, tt, vtl);
@@ -290,9 +297,10 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
     }
   }
   __syncthreads();
-  // LDS -> global: 16 lanes x 16 bytes cover one row of the tile
-  constexpr int ROWS_PER_PASS = C::NTHREADS / 16;
-  const int chunk = threadIdx.x & 15, r0 = threadIdx.x >> 4;
+  // LDS -> global: BM / 8 lanes x 16 bytes cover one row of the tile
+  constexpr int LANES_PER_ROW = C::BM / 8;
+  constexpr int ROWS_PER_PASS = C::NTHREADS / LANES_PER_ROW;
+  const int chunk = threadIdx.x % LANES_PER_ROW, r0 = threadIdx.x / LANES_PER_ROW;
 #pragma unroll 4
   for (int r = r0; r < C::BN; r += ROWS_PER_PASS) {
     const int t = n0 + r;
