@@ -119,13 +119,69 @@ def measured_context(wl, H, W):
     return ctx
 
 
+def bench_inject(args, wl, dev):
+    """e' = e + xi Proj([l; m; h]) forward + backward (dT, dP) at the workload's T and d."""
+    import torch
+    from paper_2605_08632_amd import binding as b
+    T, d, dt, F = wl.T, wl.d, args.teacher_d, 3
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed + 13)
+    mk = lambda *shape: torch.randn(*shape, generator=g, device=dev, dtype=torch.float32)
+    E = mk(T, d).to(torch.bfloat16)
+    feats = [mk(T, dt).to(torch.bfloat16) for _ in range(F)]
+    P = (mk(d, F * dt) / np.sqrt(F * dt)).to(torch.bfloat16)
+    G = mk(T, d).to(torch.bfloat16)
+    rows_per_instance = wl.K * 64
+    xi = (torch.rand(T // rows_per_instance + 1, generator=g, device=dev) >= 0.1).float()
+    xi = xi.repeat_interleave(rows_per_instance)[:T].contiguous()      # rho = 0.1, one draw per instance
+    Eout = torch.empty_like(E)
+    dP = torch.empty(d, F * dt, dtype=torch.bfloat16, device=dev)
+
+    def step():
+        b.pard2_inject_fwd(E, feats, P, xi, Eout=Eout)
+        b.pard2_inject_bwd(G, feats, xi, dP=dP)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    b.pard2_cat_kernel_timing(True)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    names = ("inject_fwd_kernel", "inject_dp_kernel")
+    per_kernel = {n: b.pard2_cat_kernel_timing_read(b.KERNEL_NAMES.index(n)) for n in names}
+    b.pard2_cat_kernel_timing(False)
+    flop = 2.0 * T * d * F * dt                      # per kernel launch (forward; dP the same)
+    k = max(names, key=lambda n: per_kernel[n][0])
+    k_ms, k_n = per_kernel[k]
+    achieved = flop / (k_ms / k_n * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "gated target-feature injection fwd+bwd tokens/s (adjacent step; not the CAT-loss metric)",
+        "value": T / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name} shape: T={T}, d={d}, {F} target features of width {dt}, rho=0.1, fwd+bwd"},
+        "executed_tflops": 2 * flop / (ms * 1e-3) / 1e12,
+        "kernel_ms_per_step": {n: per_kernel[n][0] / args.steps for n in names},
+        "roofline": {"bound": "mfma", "kernel": k, "achieved": achieved, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "avg_launch_ms": k_ms / k_n,
+                     "launches": k_n, "flop_per_launch": flop, "traffic": None},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--context", action="store_true",
                     help="also measure the MFMA-only peak and the vendor GEMM on this device (adds ~5 s)")
     ap.add_argument("--variant", default="cat",
                     help="cat (default) | decay0.8 | uniform | external | accumulate | fwd | stats | "
-                         "kd (the Eq.12 token loss: beta CE + KD against a teacher head of width --teacher-d)")
+                         "kd (the Eq.12 token loss: beta CE + KD against a teacher head of width --teacher-d) | "
+                         "inject (gated injection of 3 target features of width --teacher-d into the draft's input "
+                         "embeddings, fwd+bwd: an adjacent step, not the loss)")
     ap.add_argument("--teacher-d", type=int, default=4096, help="hidden width of the teacher head (variant kd)")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
@@ -145,6 +201,8 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.variant == "inject":
+        return bench_inject(args, wl, dev)
     desc, H, W, y, vl = make_inputs(wl, dev)
     ws = b.alloc_workspace(desc, dev)
     out = {}

@@ -198,11 +198,41 @@ int pard2_cat_kd_bwd(const pard2_cat_desc* desc, const void* H, const void* W,
                      void* dH, void* dW, int32_t accumulate_dW,
                      void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- Gated injection of target features into the draft's input embeddings (Sec.3.3) ---------
+ *
+ *   e'[t,:] = e[t,:] + xi_t * Proj([x_1[t,:]; ...; x_F[t,:]])
+ * x_1..x_F are the target model's hidden states of F layers (the paper names low / middle / high
+ * and trains with four), [.;.] concatenates along the feature axis, and xi ~ Bernoulli(1 - rho)
+ * is drawn per training instance.  Reading (the paper only calls Proj "lightweight"): Proj is one
+ * linear map without bias, P[d, F*dt] row-major, column block f multiplying x_f.  The gate is an
+ * INPUT, xi[T] fp32, one value per token row (repeat an instance's draw over its rows; any real
+ * value is accepted).  bf16 storage, fp32 accumulation; the concatenation is never formed.
+ *
+ *   T, d, dt, F   token rows, draft width, width of one feature, number of features (1..8);
+ *                 d and dt multiples of 8.
+ *   E     [T,d]   draft input embeddings, dense.      Eout [T,d] out (may alias E).
+ *   feats [F]     HOST array of F device pointers, each [T,dt] with row stride ldX (elements,
+ *                 a multiple of 8, >= dt); 16-byte aligned.
+ *   P     [d,F*dt] dense.      xi [T] fp32.
+ * Backward (the target model is frozen; the gradient of e is dEout itself):
+ *   dEout [T,d]   upstream gradient.
+ *   dT    [T,d]   out: xi * dEout, the gradient of the projected feature (also the kernel's
+ *                 staging operand: required).
+ *   dP    [d,F*dt] out (+= when accumulate_dP != 0).
+ * Same pointer, stream and error conventions as above; no workspace. */
+int pard2_inject_fwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* E,
+                     const void* const* feats, int64_t ldX, const void* P, const float* xi,
+                     void* Eout, void* stream);
+int pard2_inject_bwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* dEout,
+                     const void* const* feats, int64_t ldX, const float* xi, void* dT, void* dP,
+                     int32_t accumulate_dP, void* stream);
+
 /* Measurement aid (not part of the method).  pard2_cat_kernel_timing(1) makes every later
  * launch of the contraction kernels record a pair of HIP events on its stream;
  * pard2_cat_kernel_timing(0) switches it off; either call forgets earlier records.
  * pard2_cat_kernel_timing_read waits for the recorded launches of one kernel
- * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW, 4 two-head forward sweep, 5 two-head dZ)
+ * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW, 4 two-head forward sweep, 5 two-head dZ,
+ * 6 injection forward, 7 injection dP)
  * and returns their summed duration in milliseconds and their count.  Host pointers.  Not
  * thread-safe against concurrent launches from other host threads. */
 int pard2_cat_kernel_timing(int enable);

@@ -20,9 +20,11 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat
 EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
            "pard2_cat_weights", "pard2_cat_weights_seq", "pard2_cat_fwd", "pard2_cat_bwd",
            "pard2_cat_kd_workspace_bytes", "pard2_cat_kd_fwd", "pard2_cat_kd_bwd",
+           "pard2_inject_fwd", "pard2_inject_bwd",
            "pard2_cat_kernel_timing",
            "pard2_cat_kernel_timing_read")
-KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel", "kd_stats_kernel", "kd_dz_kernel")
+KERNEL_NAMES = ("fwd_stats_kernel", "dz_kernel", "dh_kernel", "dw_kernel", "kd_stats_kernel", "kd_dz_kernel",
+                "inject_fwd_kernel", "inject_dp_kernel")
 
 
 class Pard2Error(RuntimeError):
@@ -76,6 +78,12 @@ def lib() -> ctypes.CDLL:
     L.pard2_cat_kd_fwd.restype = ctypes.c_int
     L.pard2_cat_kd_bwd.argtypes = [D, c_void_p, c_void_p, TE] + [c_void_p] * 8 + [c_int32, c_void_p, c_size_t, c_void_p]
     L.pard2_cat_kd_bwd.restype = ctypes.c_int
+    L.pard2_inject_fwd.argtypes = [c_int32] * 4 + [c_void_p, POINTER(c_void_p), c_int64, c_void_p, c_void_p, c_void_p,
+                                                 c_void_p]
+    L.pard2_inject_fwd.restype = ctypes.c_int
+    L.pard2_inject_bwd.argtypes = [c_int32] * 4 + [c_void_p, POINTER(c_void_p), c_int64, c_void_p, c_void_p, c_void_p,
+                                                 c_int32, c_void_p]
+    L.pard2_inject_bwd.restype = ctypes.c_int
     L.pard2_cat_kernel_timing.argtypes = [ctypes.c_int]
     L.pard2_cat_kernel_timing.restype = ctypes.c_int
     L.pard2_cat_kernel_timing_read.argtypes = [ctypes.c_int, POINTER(ctypes.c_double), POINTER(c_int64)]
@@ -350,3 +358,56 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
                                 1 if accumulate_dW else 0, wp, wn, _stream())
     _check(rc, "pard2_cat_kd_bwd")
     return dH, dW
+
+
+# ---------------------------------------------------------------- gated target-feature injection (Sec.3.3)
+def _inject_args(feats, d, dev):
+    import torch
+    F = len(feats)
+    if not 1 <= F <= 8:
+        raise Pard2Error("1..8 target features")
+    T, dt = feats[0].shape
+    for f in feats:
+        _check_tensor(f, "H", torch.bfloat16, 0, dev)      # name "H": a strided 2-D operand
+        if tuple(f.shape) != (T, dt) or f.stride(1) != 1 or f.stride(0) != feats[0].stride(0):
+            raise Pard2Error("target features must share shape [T, dt] and row stride")
+    arr = (c_void_p * F)(*[f.data_ptr() for f in feats])
+    return T, dt, F, arr, feats[0].stride(0)
+
+
+def pard2_inject_fwd(E, feats, P, xi, Eout=None):
+    """e' = e + xi * Proj([x_1; ...; x_F]).  Returns Eout [T, d] bf16."""
+    import torch
+    dev = E.device
+    d = E.shape[1]
+    T, dt, F, arr, ldX = _inject_args(feats, d, dev)
+    _check_tensor(E, "E", torch.bfloat16, T * d, dev)
+    _check_tensor(P, "P", torch.bfloat16, d * F * dt, dev)
+    _check_tensor(xi, "xi", torch.float32, T, dev)
+    if tuple(E.shape) != (T, d) or tuple(P.shape) != (d, F * dt):
+        raise Pard2Error("E must be [T, d] and P [d, F*dt]")
+    Eout = torch.empty_like(E) if Eout is None else Eout
+    _check_tensor(Eout, "Eout", torch.bfloat16, T * d, dev)
+    rc = lib().pard2_inject_fwd(T, d, dt, F, _ptr(E), arr, ldX, _ptr(P), _ptr(xi), _ptr(Eout), _stream())
+    _check(rc, "pard2_inject_fwd")
+    return Eout
+
+
+def pard2_inject_bwd(dEout, feats, xi, dP=None, accumulate_dP=False):
+    """Returns (dT [T, d] = xi * dEout, dP [d, F*dt]); the gradient of e is dEout itself."""
+    import torch
+    dev = dEout.device
+    d = dEout.shape[1]
+    T, dt, F, arr, ldX = _inject_args(feats, d, dev)
+    _check_tensor(dEout, "dEout", torch.bfloat16, T * d, dev)
+    _check_tensor(xi, "xi", torch.float32, T, dev)
+    dT = torch.empty(T, d, dtype=torch.bfloat16, device=dev)
+    if dP is None:
+        if accumulate_dP:
+            raise Pard2Error("accumulate_dP needs an existing dP")
+        dP = torch.empty(d, F * dt, dtype=torch.bfloat16, device=dev)
+    _check_tensor(dP, "dP", torch.bfloat16, d * F * dt, dev)
+    rc = lib().pard2_inject_bwd(T, d, dt, F, _ptr(dEout), arr, ldX, _ptr(xi), _ptr(dT), _ptr(dP),
+                                1 if accumulate_dP else 0, _stream())
+    _check(rc, "pard2_inject_bwd")
+    return dT, dP

@@ -13,7 +13,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 BUILD = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libpard2cat.so")
-SOURCES = ["api.hip", "small_kernels.hip", "f32_kernels.hip", "bf16_kernels.hip", "kd_kernels.hip"]
+SOURCES = ["api.hip", "small_kernels.hip", "f32_kernels.hip", "bf16_kernels.hip", "kd_kernels.hip",
+           "inject_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

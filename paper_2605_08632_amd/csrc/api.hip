@@ -373,4 +373,50 @@ int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, cons
   return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
 }
 
+static int validate_inject(int32_t T, int32_t d, int32_t dt, int32_t F, int64_t ldX) {
+  if (T <= 0 || d <= 0 || dt <= 0 || F < 1 || F > 8) return PARD2_ERR_SHAPE;
+  if ((d & 7) || (dt & 7) || (ldX & 7) || ldX < dt) return PARD2_ERR_SHAPE;
+  // tile-relative byte offsets inside the kernels are 32-bit
+  if ((int64_t)F * dt * 2 * 512 > 0x7fffffffLL || ldX * 2 * 512 > 0x7fffffffLL || (int64_t)d * 2 * 512 > 0x7fffffffLL)
+    return PARD2_ERR_SHAPE;
+  return PARD2_OK;
+}
+
+static int gather_feats(const void* const* feats, int F, InjectFeats* out) {
+  for (int f = 0; f < 8; ++f) out->p[f] = nullptr;
+  for (int f = 0; f < F; ++f) {
+    if (!feats[f]) return PARD2_ERR_NULL;
+    if (misaligned16(feats[f])) return PARD2_ERR_SHAPE;
+    out->p[f] = feats[f];
+  }
+  return PARD2_OK;
+}
+
+int pard2_inject_fwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* E, const void* const* feats, int64_t ldX,
+                     const void* P, const float* xi, void* Eout, void* stream) {
+  int rc = validate_inject(T, d, dt, F, ldX);
+  if (rc != PARD2_OK) return rc;
+  if (!E || !feats || !P || !xi || !Eout) return PARD2_ERR_NULL;
+  if (misaligned16(E) || misaligned16(P) || misaligned16(Eout)) return PARD2_ERR_SHAPE;
+  InjectFeats fs;
+  if ((rc = gather_feats(feats, F, &fs)) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  return launch_inject_fwd(E, fs, ldX, P, xi, T, d, dt, F, Eout, (hipStream_t)stream) == hipSuccess ? PARD2_OK
+                                                                                                  : PARD2_ERR_LAUNCH;
+}
+
+int pard2_inject_bwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* dEout, const void* const* feats,
+                     int64_t ldX, const float* xi, void* dT, void* dP, int32_t accumulate_dP, void* stream) {
+  int rc = validate_inject(T, d, dt, F, ldX);
+  if (rc != PARD2_OK) return rc;
+  if (!dEout || !feats || !xi || !dT || !dP) return PARD2_ERR_NULL;
+  if (misaligned16(dEout) || misaligned16(dT) || misaligned16(dP)) return PARD2_ERR_SHAPE;
+  InjectFeats fs;
+  if ((rc = gather_feats(feats, F, &fs)) != PARD2_OK) return rc;
+  if ((rc = check_arch()) != PARD2_OK) return rc;
+  return launch_inject_bwd(dEout, fs, ldX, xi, T, d, dt, F, dT, dP, accumulate_dP, (hipStream_t)stream) == hipSuccess
+             ? PARD2_OK
+             : PARD2_ERR_LAUNCH;
+}
+
 }  // extern "C"

@@ -11,7 +11,8 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // Optional per-kernel timing (off by default): when switched on through
 // pard2_cat_kernel_timing(), every launch of one of the contraction kernels is
 // bracketed by a pair of HIP events on its stream.
-enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_KD_STATS = 4, KT_KD_DZ = 5, KT_COUNT = 6 };
+enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_KD_STATS = 4, KT_KD_DZ = 5,
+                KT_INJECT_FWD = 6, KT_INJECT_DP = 7, KT_COUNT = 8 };
 void kt_begin(int id, hipStream_t s);
 void kt_end(int id, hipStream_t s);
 
@@ -125,5 +126,14 @@ BwdPlanF32 plan_bwd_f32(int T, int d, int V);
 hipError_t launch_bwd_f32(const BwdPlanF32& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                           const int32_t* y, const float* lse, const float* g, int T, int d, int V,
                           void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s);
+
+// ---- gated injection of target features into the draft's input embeddings (Sec.3.3), bf16
+struct InjectFeats {
+  const void* p[8];   // F feature tensors [T, dt], common row stride
+};
+hipError_t launch_inject_fwd(const void* E, const InjectFeats& feats, int64_t ldX, const void* P, const float* xi,
+                             int T, int d, int dt, int F, void* Eout, hipStream_t s);
+hipError_t launch_inject_bwd(const void* dEout, const InjectFeats& feats, int64_t ldX, const float* xi, int T, int d,
+                             int dt, int F, void* dT, void* dP, int accumulate, hipStream_t s);
 
 }  // namespace pard2

@@ -119,6 +119,21 @@ def test_kd_entry_points_validate_on_the_host(b):
     assert L.pard2_cat_kd_bwd(ctypes.byref(desc), one, one, ctypes.byref(te), *([None] * 8), 0, None, 0, None) == -1
 
 
+def test_inject_entry_points_validate_on_the_host(b):
+    L = b.lib()
+    one = 256
+    feats = (ctypes.c_void_p * 3)(one, one, one)
+    # only calls that are rejected before any launch: the pointers here are not device memory
+    assert L.pard2_inject_fwd(64, 60, 32, 3, one, feats, 32, one, one, one, None) == -2     # d % 8
+    assert L.pard2_inject_fwd(64, 64, 32, 9, one, feats, 32, one, one, one, None) == -2     # F > 8
+    assert L.pard2_inject_fwd(64, 64, 32, 3, one, feats, 24, one, one, one, None) == -2     # stride < dt
+    assert L.pard2_inject_fwd(64, 64, 32, 3, None, feats, 32, one, one, one, None) == -1
+    assert L.pard2_inject_fwd(64, 64, 32, 3, one, None, 32, one, one, one, None) == -1
+    hole = (ctypes.c_void_p * 3)(one, None, one)
+    assert L.pard2_inject_bwd(64, 64, 32, 3, one, hole, 32, one, one, one, 0, None) == -1
+    assert L.pard2_inject_bwd(64, 64, 32, 3, one, feats, 32, one, None, one, 0, None) == -1
+
+
 def test_binding_raises_without_library(b, monkeypatch, tmp_path):
     monkeypatch.setattr(b, "_lib", None)
     monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "missing.so"))
