@@ -183,6 +183,9 @@ def main():
                          "inject (gated injection of 3 target features of width --teacher-d into the draft's input "
                          "embeddings, fwd+bwd: an adjacent step, not the loss)")
     ap.add_argument("--teacher-d", type=int, default=4096, help="hidden width of the teacher head (variant kd)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step from a captured HIP graph (launch gaps removed); the per-kernel event "
+                         "timing is then taken from an eager pass of the same steps run just before")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
@@ -274,6 +277,25 @@ def main():
     ms = e0.elapsed_time(e1) / args.steps
     per_kernel = [b.pard2_cat_kernel_timing_read(k) for k in range(len(b.KERNEL_NAMES))]
     b.pard2_cat_kernel_timing(False)
+    if args.graph:                              # same K steps again, as one graph replay per step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms_eager, ms = ms, e0.elapsed_time(e1) / args.steps
 
     if args.calib_copy_mib > 0:
         src = torch.empty(args.calib_copy_mib << 20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -322,6 +344,9 @@ def main():
                      "flop_per_launch": flops_kernel_per_launch, "traffic": traffic,
                      "traffic_detail": traffic_detail},
     }
+    if args.graph:
+        res["config"]["launch"] = "HIP graph replay"
+        res["ms_per_step_eager"] = ms_eager
     if args.context:
         res["context"] = measured_context(wl, H, W)
     if args.cpu_blocks > 0 and args.variant == "cat":

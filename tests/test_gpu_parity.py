@@ -276,3 +276,46 @@ def test_strided_inputs():
     g1 = b.pard2_cat_bwd(d1, H, W, y, o1["lse"], o1["w"])
     g2 = b.pard2_cat_bwd(d2, Hs[:, :p.d], Ws[:, :p.d], y, o2["lse"], o2["w"])
     assert torch.equal(g1[0], g2[0]) and torch.equal(g1[1], g2[1])
+
+
+def test_hip_graph_capture_and_replay():
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no
+    synchronisation, no memset nodes), so forward + backward can be captured in a HIP graph.
+    Every replay, with eager work and synchronisation in between, must reproduce the eager
+    result bit for bit."""
+    p = Hh.build_problem(40, 8, 256, 20000, "bf16", seed=37, ragged_frac=0.2)     # two vocabulary chunks
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=0.1)
+    ws = b.alloc_workspace(desc, H.device)
+    ref = b.pard2_cat_fwd(desc, H, W, y, valid_len=vl, workspace=ws)
+    rdH, rdW = b.pard2_cat_bwd(desc, H, W, y, ref["lse"], ref["w"], valid_len=vl, workspace=ws)
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in ref.items()}
+
+    out = {k: torch.zeros_like(v) for k, v in ref.items()}
+    dH, dW = torch.zeros_like(rdH), torch.zeros_like(rdW)
+
+    def step():
+        o = b.pard2_cat_fwd(desc, H, W, y, valid_len=vl, workspace=ws, out=out)
+        b.pard2_cat_bwd(desc, H, W, y, o["lse"], o["w"], valid_len=vl, dH=dH, dW=dW, workspace=ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                           # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        step()
+    for rep in range(3):
+        for t in list(out.values()) + [dH, dW]:          # eager work between replays: wipe the outputs
+            t.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ref:
+            assert torch.equal(out[k], ref[k]), (rep, k)
+        assert torch.equal(dH, rdH) and torch.equal(dW, rdW), rep
