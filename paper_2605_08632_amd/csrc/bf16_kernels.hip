@@ -19,6 +19,20 @@ namespace pard2 {
 #endif
 using Cfg = TileCfg<PARD2_TILE>;
 
+// Measurement aid, compiled in only with -DPARD2_CLOCK_PROBE: one wavefront of workgroup 0 prints the
+// shader clock its kernel ran at (cycle counter over the constant-rate wall counter).  The matrix cores
+// are power-limited: the clock a kernel sustains depends on what it keeps busy and on the data.
+#ifdef PARD2_CLOCK_PROBE
+#define PARD2_PROBE_BEGIN const long long probe_c0 = clock64(), probe_w0 = wall_clock64();
+#define PARD2_PROBE_END(name)                                                                      \
+  if (blockIdx.x == 0 && threadIdx.x == 0)                                                         \
+    printf("clock probe %s: %lld cycles / %lld wall ticks\n", name, (long long)(clock64() - probe_c0), \
+           (long long)(wall_clock64() - probe_w0));
+#else
+#define PARD2_PROBE_BEGIN
+#define PARD2_PROBE_END(name)
+#endif
+
 // ------------------------------------------------------------------------------------
 // Forward sweep (head contraction of Eq.4/5 + online log-softmax of the log P in Eq.11).
 // A workgroup owns BN token rows and one of `nsplit` vocabulary ranges; it walks the
@@ -34,6 +48,7 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
                                                                 int nTt, int nVt, int nsplit, float2* __restrict__ ms,
                                                                 int32_t* __restrict__ idx, float* __restrict__ zy) {
   extern __shared__ __align__(16) char smem[];
+  PARD2_PROBE_BEGIN
   const WavePos<C> wp;
   int tt, sp;
   banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, 8, tt, sp);
@@ -133,6 +148,7 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
       idx[(int64_t)t * nsplit + sp] = a.idx;
     }
   }
+  PARD2_PROBE_END("fwd_stats_kernel")
 }
 
 // ------------------------------------------------------------------------------------
@@ -253,6 +269,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
                                                          float* __restrict__ dHacc, float* __restrict__ dHpart,
                                                          __bf16* __restrict__ dH, int first, int last) {
   extern __shared__ __align__(16) char smem[];
+  PARD2_PROBE_BEGIN
   const WavePos<C> wp;
   const int id = xcd_contiguous_id(blockIdx.x, gridDim.x);
   const int ntiles = nIt * nTt;
@@ -293,6 +310,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dh_kernel(const __bf16* __restric
         }
       }
   }
+  PARD2_PROBE_END("dh_kernel")
 }
 
 // dHacc (+)= sum over slices of dHpart, in slice order; the last chunk writes bf16 dH instead.
