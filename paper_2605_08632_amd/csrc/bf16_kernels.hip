@@ -18,6 +18,13 @@ namespace pard2 {
 #define PARD2_TILE 256, 256, 2, 4
 #endif
 using Cfg = TileCfg<PARD2_TILE>;
+// token tiles per band of the tile rasterisation (how many token tiles share a vocabulary tile inside an XCD)
+#ifndef PARD2_BAND_FWD
+#define PARD2_BAND_FWD 8
+#endif
+#ifndef PARD2_BAND_DZ
+#define PARD2_BAND_DZ 8
+#endif
 
 // Measurement aid, compiled in only with -DPARD2_CLOCK_PROBE: one wavefront of workgroup 0 prints the
 // shader clock its kernel ran at (cycle counter over the constant-rate wall counter).  The matrix cores
@@ -51,7 +58,7 @@ __global__ __launch_bounds__(C::NTHREADS) void fwd_stats_kernel(const __bf16* __
   PARD2_PROBE_BEGIN
   const WavePos<C> wp;
   int tt, sp;
-  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, 8, tt, sp);
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, PARD2_BAND_FWD, tt, sp);
   const int n0 = tt * C::BN;
   const int vt_begin = (int)((int64_t)sp * nVt / nsplit), vt_end = (int)((int64_t)(sp + 1) * nVt / nsplit);
 
@@ -173,7 +180,7 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int tt, vtl;
-  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, 8, tt, vtl);
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, PARD2_BAND_DZ, tt, vtl);
   const int n0 = tt * C::BN, m0 = (vt0 + vtl) * C::BM, c0 = vtl * C::BM;
 
   f32x16 acc[C::MI][C::NI];
