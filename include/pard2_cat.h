@@ -151,7 +151,7 @@ int pard2_cat_bwd(const pard2_cat_desc* desc, const void* H, const void* W, cons
                   const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW,
                   void* workspace, size_t workspace_bytes, void* stream);
 
-/* ---- The full token loss of Eq.12: s_{n,k} (beta CE + KD), bf16 storage only ----------------
+/* ---- The full token loss of Eq.12: s_{n,k} (beta CE + KD) ------------------------------------
  *
  * Eq.12 adds a distillation term to the weighted cross-entropy without defining it.  The
  * reading built here: KD_t = KL(p_t || q_t) = sum_v p_t(v) (log p_t(v) - log q_t(v)) at
@@ -165,7 +165,8 @@ int pard2_cat_bwd(const pard2_cat_desc* desc, const void* H, const void* W, cons
  *
  * The teacher (host struct, device pointers): H [T, d] hidden states gathered token-major by the
  * caller (row t = the target model's state that predicts token t), W [V, d] its LM head, both
- * bf16, 16-byte aligned, d and the strides multiples of 8.  d may differ from the draft's.
+ * of storage type desc->dtype (bf16: 16-byte aligned, d and the strides multiples of 8).  d may
+ * differ from the draft's.
  */
 typedef struct {
   const void* H;      /* [T, d]  row stride ldH (elements) */
@@ -183,7 +184,7 @@ size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* desc, int32_t teacher_
  *                  ignored rows use c = 1).
  *   lse_t     [T]  out: logsumexp of the teacher's rows (needed by the backward).
  *   kd        [T]  out or NULL: KL(p_t || q_t) per row.
- * desc->dtype must be PARD2_BF16 (else PARD2_ERR_DTYPE); desc->beta must be >= 0. */
+ * desc->beta must be >= 0 (else PARD2_ERR_HYPER). */
 int pard2_cat_kd_fwd(const pard2_cat_desc* desc, const void* H, const void* W,
                      const pard2_kd_teacher* teacher, const int32_t* y, const float* conf_in,
                      const int32_t* valid_len, float* loss, float* lse, float* lse_t, float* logp_y,

@@ -285,9 +285,9 @@ def alloc_kd_workspace(desc: pard2_cat_desc, teacher_d: int, device):
 
 
 def _teacher(desc, Ht, Wt, dev):
-    import torch
-    _check_tensor(Ht, "H", torch.bfloat16, 0, dev)
-    _check_tensor(Wt, "W", torch.bfloat16, 0, dev)
+    td = _torch_dtype(desc)
+    _check_tensor(Ht, "H", td, 0, dev)
+    _check_tensor(Wt, "W", td, 0, dev)
     if Ht.stride(-1) != 1 or Wt.stride(-1) != 1 or Ht.shape[0] != desc.T or Wt.shape[0] != desc.V or \
             Ht.shape[1] != Wt.shape[1]:
         raise Pard2Error("teacher H/W shapes do not match the descriptor")
@@ -299,8 +299,9 @@ def pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=None, valid_len=None, worksp
     lse_t, logp_y, kd, w, argmax, accept_len, exp_len, dev_status."""
     import torch
     dev = H.device
-    _check_tensor(H, "H", torch.bfloat16, 0, dev)
-    _check_tensor(W, "W", torch.bfloat16, 0, dev)
+    td = _torch_dtype(desc)
+    _check_tensor(H, "H", td, 0, dev)
+    _check_tensor(W, "W", td, 0, dev)
     if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
         raise Pard2Error("H/W strides do not match the descriptor")
     if tuple(H.shape) != (desc.T, desc.d) or tuple(W.shape) != (desc.V, desc.d):
@@ -334,8 +335,9 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
     """Backward of pard2_cat_kd_fwd's loss into the draft's H and W.  Returns (dH, dW)."""
     import torch
     dev = H.device
-    _check_tensor(H, "H", torch.bfloat16, 0, dev)
-    _check_tensor(W, "W", torch.bfloat16, 0, dev)
+    td = _torch_dtype(desc)
+    _check_tensor(H, "H", td, 0, dev)
+    _check_tensor(W, "W", td, 0, dev)
     if H.stride(-1) != 1 or W.stride(-1) != 1 or H.stride(0) != desc.ldH or W.stride(0) != desc.ldW:
         raise Pard2Error("H/W strides do not match the descriptor")
     te = _teacher(desc, Ht, Wt, dev)
@@ -344,13 +346,13 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
         _check_tensor(t, name, torch.float32, desc.T, dev)
     _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
     _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
-    dH = torch.empty(desc.T, desc.d, dtype=torch.bfloat16, device=dev) if dH is None else dH
+    dH = torch.empty(desc.T, desc.d, dtype=td, device=dev) if dH is None else dH
     if dW is None:
         if accumulate_dW:
             raise Pard2Error("accumulate_dW needs an existing dW")
-        dW = torch.empty(desc.V, desc.d, dtype=torch.bfloat16, device=dev)
-    _check_tensor(dH, "dH", torch.bfloat16, desc.T * desc.d, dev)
-    _check_tensor(dW, "dW", torch.bfloat16, desc.V * desc.d, dev)
+        dW = torch.empty(desc.V, desc.d, dtype=td, device=dev)
+    _check_tensor(dH, "dH", td, desc.T * desc.d, dev)
+    _check_tensor(dW, "dW", td, desc.V * desc.d, dev)
     ws = alloc_kd_workspace(desc, te.d, dev) if workspace is None else workspace
     wp, wn = _ws_args(ws)
     rc = lib().pard2_cat_kd_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(valid_len),

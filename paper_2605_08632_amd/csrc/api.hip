@@ -79,7 +79,7 @@ struct KdFwdPlan {
 
 KdFwdPlan plan_kd_fwd(const pard2_cat_desc* d) {
   KdFwdPlan p{};
-  p.P = kd_num_partials_bf16(d->T, d->V);
+  p.P = d->dtype == PARD2_BF16 ? kd_num_partials_bf16(d->T, d->V) : fwd_num_partials_f32(d->T, d->V);
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
   p.off_ms = take((size_t)d->T * p.P * sizeof(float2));
@@ -101,9 +101,9 @@ KdFwdPlan plan_kd_fwd(const pard2_cat_desc* d) {
 int validate_kd(const pard2_cat_desc* d, int32_t dt, int64_t ldHt, int64_t ldWt) {
   int rc = pard2_cat_validate(d);
   if (rc != PARD2_OK) return rc;
-  if (d->dtype != PARD2_BF16) return PARD2_ERR_DTYPE;
   if (!(d->beta >= 0.f)) return PARD2_ERR_HYPER;
-  if (dt <= 0 || (dt & 7) || ldHt < dt || ldWt < dt || (ldHt & 7) || (ldWt & 7)) return PARD2_ERR_SHAPE;
+  if (dt <= 0 || ldHt < dt || ldWt < dt) return PARD2_ERR_SHAPE;
+  if (d->dtype == PARD2_BF16 && ((dt & 7) || (ldHt & 7) || (ldWt & 7))) return PARD2_ERR_SHAPE;
   if (ldHt * 2 * 512 > 0x7fffffffLL || ldWt * 2 * 512 > 0x7fffffffLL) return PARD2_ERR_SHAPE;
   return PARD2_OK;
 }
@@ -300,7 +300,7 @@ int pard2_cat_bwd(const pard2_cat_desc* d, const void* H, const void* W, const i
 
 size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* d, int32_t teacher_d) {
   if (validate_kd(d, teacher_d, teacher_d, teacher_d) != PARD2_OK) return 0;
-  const size_t f = plan_kd_fwd(d).total, b = plan_bwd_bf16(d->T, d->d, d->V).total;
+  const size_t f = plan_kd_fwd(d).total, b = bwd_bytes(d);
   return f > b ? f : b;
 }
 
@@ -312,7 +312,8 @@ int pard2_cat_kd_fwd(const pard2_cat_desc* d, const void* H, const void* W, cons
   int rc = validate_kd(d, te->d, te->ldH, te->ldW);
   if (rc != PARD2_OK) return rc;
   if (!H || !W || !te->H || !te->W || !y || !lse || !lse_t || !logp_y) return PARD2_ERR_NULL;
-  if (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W)) return PARD2_ERR_SHAPE;
+  if (d->dtype == PARD2_BF16 && (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W)))
+    return PARD2_ERR_SHAPE;
   const KdFwdPlan p = plan_kd_fwd(d);
   if ((rc = check_workspace(workspace, workspace_bytes, p.total)) != PARD2_OK) return rc;
   if ((rc = check_arch()) != PARD2_OK) return rc;
@@ -329,7 +330,9 @@ int pard2_cat_kd_fwd(const pard2_cat_desc* d, const void* H, const void* W, cons
   const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, nullptr, d->beta};
 
   if (dev_status) hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dev_status, 0);
-  if (launch_kd_stats_bf16(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s) != hipSuccess) return PARD2_ERR_LAUNCH;
+  const hipError_t e = d->dtype == PARD2_BF16 ? launch_kd_stats_bf16(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s)
+                                              : launch_kd_stats_f32(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s);
+  if (e != hipSuccess) return PARD2_ERR_LAUNCH;
   if (launch_kd_combine(st, y, conf_in, d->T, d->V, d->ignore_index, d->beta, lse, lse_t, logp_y, kd, tok, argmax, conf,
                         hit, dev_status, s) != hipSuccess)
     return PARD2_ERR_LAUNCH;
@@ -354,22 +357,29 @@ int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, cons
   int rc = validate_kd(d, te->d, te->ldH, te->ldW);
   if (rc != PARD2_OK) return rc;
   if (!H || !W || !te->H || !te->W || !y || !lse || !lse_t || !w || !dH || !dW) return PARD2_ERR_NULL;
-  if (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W) || misaligned16(dH) ||
-      misaligned16(dW))
+  if (d->dtype == PARD2_BF16 && (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W) ||
+                                 misaligned16(dH) || misaligned16(dW)))
     return PARD2_ERR_SHAPE;
-  const BwdPlanBf16 p = plan_bwd_bf16(d->T, d->d, d->V);
-  if ((rc = check_workspace(workspace, workspace_bytes, p.total)) != PARD2_OK) return rc;
+  if ((rc = check_workspace(workspace, workspace_bytes, bwd_bytes(d))) != PARD2_OK) return rc;
   if ((rc = check_arch()) != PARD2_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  float* g = (float*)(ws + p.off_g);
-  // g_t = grad_loss w_t / N: beta sits inside the bracket of Eq.12
-  if (launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, 1.f, g, s) !=
-      hipSuccess)
-    return PARD2_ERR_LAUNCH;
   const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, lse_t, d->beta};
-  const hipError_t e =
-      launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
+  // g_t = grad_loss w_t / N: beta sits inside the bracket of Eq.12
+  hipError_t e;
+  if (d->dtype == PARD2_BF16) {
+    const BwdPlanBf16 p = plan_bwd_bf16(d->T, d->d, d->V);
+    float* g = (float*)(ws + p.off_g);
+    e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, 1.f, g, s);
+    if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
+  } else {
+    const BwdPlanF32 p = plan_bwd_f32(d->T, d->d, d->V);
+    float* g = (float*)(ws + p.off_g);
+    e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, 1.f, g, s);
+    if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+    e = launch_bwd_f32(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
+  }
   return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
 }
 

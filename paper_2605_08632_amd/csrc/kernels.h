@@ -104,6 +104,8 @@ struct KdStatsOut {
   float* zy_t;
 };
 int kd_num_partials_bf16(int T, int V);
+hipError_t launch_kd_stats_f32(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& teacher,
+                               const int32_t* y, int T, int d, int V, KdStatsOut out, hipStream_t s);
 hipError_t launch_kd_stats_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& teacher,
                                 const int32_t* y, int T, int d, int V, KdStatsOut out, hipStream_t s);
 // Merge partials of both heads: lse, lse_t, log q(y), KL(p || q), argmax, confidence (given, or the
@@ -125,7 +127,8 @@ struct BwdPlanF32 {
 BwdPlanF32 plan_bwd_f32(int T, int d, int V);
 hipError_t launch_bwd_f32(const BwdPlanF32& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                           const int32_t* y, const float* lse, const float* g, int T, int d, int V,
-                          void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s);
+                          void* dH, void* dW, int accumulate_dW, char* ws, hipStream_t s,
+                          const KdTeacher* kd = nullptr);
 
 // ---- gated injection of target features into the draft's input embeddings (Sec.3.3), bf16
 struct InjectFeats {

@@ -128,7 +128,7 @@ def make_head(seed: int, T: int, d: int, V: int, dtype: str, w_scale: float = 4.
 
 
 def make_teacher(seed: int, head: Head, dt: int, noise: float = 2.0) -> Head:
-    """Teacher hidden states Ht[T, dt] and head Wt[V, dt] (bf16) for the distillation term.
+    """Teacher hidden states Ht[T, dt] and head Wt[V, dt] (storage type of `head`) for the distillation term.
 
     A target model is wider than its drafter and its distribution resembles the drafter's
     without equalling it.  For dt > d the teacher extends the draft head's operands,
@@ -136,15 +136,15 @@ def make_teacher(seed: int, head: Head, dt: int, noise: float = 2.0) -> Head:
     so that its logits are the draft's plus independent noise of standard deviation ~`noise`.
     For dt <= d an unrelated head of width dt is drawn instead.
     """
-    if head.dtype != "bf16":
-        raise ValueError("the teacher recipe is defined for bf16 heads")
     T, d = head.H.shape
     V = head.W.shape[0]
     if dt <= d:
-        return make_head(int(np.random.default_rng([seed, 11]).integers(1 << 30)), T, dt, V, "bf16")
+        return make_head(int(np.random.default_rng([seed, 11]).integers(1 << 30)), T, dt, V, head.dtype)
     rng = np.random.default_rng([seed, 12])
     E = _unit_rms_rows(rng.standard_normal((T, dt - d), dtype=np.float32)) * np.float32(noise)
     F = rng.standard_normal((V, dt - d), dtype=np.float32) * np.float32(1.0 / np.sqrt(dt - d))
+    if head.dtype == "fp32":
+        return Head(np.concatenate([head.H, E], axis=1), np.concatenate([head.W, F], axis=1), None, None, "fp32")
     hb = np.concatenate([head.H_bits, f32_to_bf16_bits(E)], axis=1)
     wb = np.concatenate([head.W_bits, f32_to_bf16_bits(F)], axis=1)
     return Head(bf16_bits_to_f32(hb), bf16_bits_to_f32(wb), hb, wb, "bf16")

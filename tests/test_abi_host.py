@@ -102,7 +102,7 @@ def test_kd_entry_points_validate_on_the_host(b):
     desc = b.make_desc(64, 64, 512, 8, 8, b.PARD2_BF16)
     assert b.pard2_cat_kd_workspace_bytes(desc, 128) > 0
     assert b.pard2_cat_kd_workspace_bytes(desc, 100) == 0            # teacher width not a multiple of 8
-    assert b.pard2_cat_kd_workspace_bytes(b.make_desc(64, 64, 512, 8, 8, b.PARD2_FP32), 128) == 0
+    assert b.pard2_cat_kd_workspace_bytes(b.make_desc(64, 60, 513, 8, 8, b.PARD2_FP32), 100) > 0   # fp32: no multiple-of-8 rule
     assert b.pard2_cat_kd_workspace_bytes(b.make_desc(64, 64, 512, 8, 8, b.PARD2_BF16, beta=-0.1), 128) == 0
     assert ctypes.sizeof(b.pard2_kd_teacher) == 40
     one = 256
@@ -110,8 +110,8 @@ def test_kd_entry_points_validate_on_the_host(b):
     # null teacher / null data pointers / fp32 storage / missing workspace: all rejected before any launch
     assert L.pard2_cat_kd_fwd(ctypes.byref(desc), one, one, None, *([None] * 13), None, 0, None) == -1
     assert L.pard2_cat_kd_fwd(ctypes.byref(desc), None, one, ctypes.byref(te), *([None] * 13), None, 0, None) == -1
-    f32 = b.make_desc(64, 64, 512, 8, 8, b.PARD2_FP32)
-    assert L.pard2_cat_kd_fwd(ctypes.byref(f32), one, one, ctypes.byref(te), *([None] * 13), None, 0, None) == -3
+    neg = b.make_desc(64, 64, 512, 8, 8, b.PARD2_BF16, beta=-1.0)
+    assert L.pard2_cat_kd_fwd(ctypes.byref(neg), one, one, ctypes.byref(te), *([None] * 13), None, 0, None) == -6
     args = [one, None, None, None, one, one, one] + [None] * 6        # y .. dev_status
     assert L.pard2_cat_kd_fwd(ctypes.byref(desc), one, one, ctypes.byref(te), *args, None, 0, None) == -4
     bad = b.pard2_kd_teacher(one, one, 64, 128, 128, 0)              # stride below the teacher's width

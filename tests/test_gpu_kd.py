@@ -28,8 +28,14 @@ def _bf16_dev(bits, device="cuda:0"):
     return torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(device)
 
 
-def build_kd_problem(B, K, d, dt, V, seed, teacher="extend", **kw):
-    p = Hh.build_problem(B, K, d, V, "bf16", seed, **kw)
+def _teacher_dev(p, device="cuda:0"):
+    if p.dtype == "bf16":
+        return _bf16_dev(p.teacher.H_bits, device), _bf16_dev(p.teacher.W_bits, device)
+    return torch.from_numpy(p.teacher.H).to(device), torch.from_numpy(p.teacher.W).to(device)
+
+
+def build_kd_problem(B, K, d, dt, V, seed, teacher="extend", dtype="bf16", **kw):
+    p = Hh.build_problem(B, K, d, V, dtype, seed, **kw)
     p.teacher = p.head if teacher == "same" else synth.make_teacher(seed, p.head, dt)
     p.dt = p.teacher.H.shape[1]
     p.kd_stats = KD.kd_stats(p.head.H, p.W64, p.teacher.H, p.teacher.W.astype(np.float64), p.y)
@@ -40,9 +46,9 @@ def run_kd_case(p, beta=0.1, mode=O.W_CAT, gamma=1.0, reduction=O.RED_MEAN_VALID
                 accumulate=False):
     b = _binding()
     H, W, y, vl, conf = Hh.to_device(p)
-    Ht, Wt = _bf16_dev(p.teacher.H_bits), _bf16_dev(p.teacher.W_bits)
-    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, weight_mode=mode, reduction=reduction, beta=beta,
-                       gamma=gamma)
+    Ht, Wt = _teacher_dev(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16 if p.dtype == "bf16" else b.PARD2_FP32,
+                       weight_mode=mode, reduction=reduction, beta=beta, gamma=gamma)
     ws = b.alloc_kd_workspace(desc, p.dt, H.device)
     beta32, gamma32 = float(np.float32(beta)), float(np.float32(gamma))
     ref = KD.cat_kd_forward(p.head.H, None, p.teacher.H, None, p.y, p.B, p.K,
@@ -51,7 +57,7 @@ def run_kd_case(p, beta=0.1, mode=O.W_CAT, gamma=1.0, reduction=O.RED_MEAN_VALID
     out = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=conf if external else None, valid_len=vl, workspace=ws)
     torch.cuda.synchronize()
     g = Hh.check_forward(out, ref, p, stats_only=True)
-    tol = Hh.TOL["bf16"]
+    tol = Hh.TOL[p.dtype]
     np.testing.assert_allclose(g["lse_t"], ref["lse_t"], rtol=tol["stat"], atol=tol["stat"])
     np.testing.assert_allclose(g["kd"], ref["kd"], rtol=3 * tol["stat"], atol=3 * tol["stat"])
     np.testing.assert_allclose(g["w"], ref["w"], rtol=10 * tol["stat"], atol=1e-30)
@@ -64,12 +70,12 @@ def run_kd_case(p, beta=0.1, mode=O.W_CAT, gamma=1.0, reduction=O.RED_MEAN_VALID
     dW0 = None
     if accumulate:
         dW0 = torch.from_numpy(np.random.default_rng(5).standard_normal((p.V, p.d)).astype(np.float32) *
-                               np.float32(np.abs(rb["dW"]).max())).to(torch.bfloat16).to(H.device)
+                               np.float32(np.abs(rb["dW"]).max())).to(H.dtype).to(H.device)
     dH, dW = b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, out["lse"], out["lse_t"], out["w"], valid_len=vl, grad_loss=gl,
                                 dW=None if dW0 is None else dW0.clone(), accumulate_dW=accumulate, workspace=ws)
     torch.cuda.synchronize()
     ref_dW = rb["dW"] if dW0 is None else rb["dW"] + dW0.float().cpu().numpy().astype(np.float64)
-    eH, eW = Hh.check_grads(dH, dW, rb["dH"], ref_dW, "bf16")
+    eH, eW = Hh.check_grads(dH, dW, rb["dH"], ref_dW, p.dtype)
     inv = ~O.valid_mask(p.y, p.B, p.K, p.valid_len)
     if inv.any():
         assert not dH.float().cpu().numpy()[inv].any()
@@ -89,6 +95,16 @@ def test_kd_ragged(kd_ragged, variant):
           "decay": dict(mode=O.W_DECAY, gamma=0.8), "negative_gradloss": dict(grad_loss=-2.0),
           "accumulate": dict(accumulate=True)}[variant]
     run_kd_case(kd_ragged, **kw)
+
+
+@pytest.mark.parametrize("variant", ["default", "beta1_sum_external", "accumulate_gradloss"])
+def test_kd_fp32_storage(variant):
+    """fp32 storage: plain fp32 FMA contractions, results track the fp64 definition to ~1e-6, so the
+    two-head arithmetic is checked at 1e-5 instead of bf16's 1e-2.  Nothing divides the 64-wide tiles."""
+    p = build_kd_problem(13, 5, 100, 148, 1001, seed=41, dtype="fp32", ragged_frac=0.3, drop_some=True)
+    kw = {"default": dict(), "beta1_sum_external": dict(beta=1.0, reduction=O.RED_SUM, external=True),
+          "accumulate_gradloss": dict(accumulate=True, grad_loss=-1.5)}[variant]
+    run_kd_case(p, **kw)
 
 
 def test_kd_multi_tile_k16():
