@@ -168,3 +168,8 @@ def test_kd_medium_sampled():
     # per-tensor scale: the full tensors' max magnitude is not known to the oracle here, so the sampled
     # rows' own max is the denominator (a stricter test)
     Hh.check_grads(dH, dW, rb["dH"], rb["dW"], "bf16", rows=rows, vrows=vrows)
+
+
+def test_kd_minimum_sizes():
+    for B, K, d, dt, V, seed in [(1, 1, 8, 16, 2, 61), (2, 3, 8, 8, 3, 62)]:
+        run_kd_case(build_kd_problem(B, K, d, dt, V, seed=seed), beta=1.0)

@@ -319,3 +319,13 @@ def test_hip_graph_capture_and_replay():
         for k in ref:
             assert torch.equal(out[k], ref[k]), (rep, k)
         assert torch.equal(dH, rdH) and torch.equal(dW, rdW), rep
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_minimum_sizes(dtype):
+    """One token, one block, the smallest hidden width the bf16 path takes (8), two vocabulary ids;
+    then a few tokens with K = 1 and V = 3."""
+    for B, K, d, V, seed in [(1, 1, 8, 2, 51), (3, 1, 8, 3, 52), (1, 5, 16, 2, 53)]:
+        p = Hh.build_problem(B, K, d, V, dtype, seed=seed)
+        _run_case(p, beta=1.0)
+        _run_case(p, external=True)
