@@ -139,3 +139,23 @@ def test_binding_raises_without_library(b, monkeypatch, tmp_path):
     monkeypatch.setattr(b, "LIB_PATH", str(tmp_path / "missing.so"))
     with pytest.raises(b.Pard2Error):
         b.lib()
+
+
+def test_header_is_plain_c_and_links(b, tmp_path):
+    """gcc -std=c99 -pedantic compiles a C program against include/pard2_cat.h, links the library and runs
+    its host-only calls (layout of the two structs, validation, refusal of null pointers)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("gcc not found")
+    b.lib()                                              # the library must exist
+    exe = str(tmp_path / "abi_host_check")
+    libdir = os.path.dirname(b.LIB_PATH)
+    src = os.path.join(ROOT, "tests", "c", "abi_host_check.c")
+    cmd = ["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), src,
+           "-o", exe, "-L", libdir, "-lpard2cat", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+           "-Wl,--allow-shlib-undefined"]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "abi_host_check ok" in r.stdout, r.stdout + r.stderr
