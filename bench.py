@@ -209,8 +209,10 @@ def main():
     desc, H, W, y, vl = make_inputs(wl, dev)
     ws = b.alloc_workspace(desc, dev)
     out = {}
-    dH = torch.empty(wl.T, wl.d, dtype=torch.bfloat16, device=dev)
-    dW = torch.empty(wl.V, wl.d, dtype=torch.bfloat16, device=dev)
+    # gradient outputs rotate between two buffers from step to step (caches are not flushed otherwise)
+    dHs = [torch.empty(wl.T, wl.d, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    dWs = [torch.empty(wl.V, wl.d, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+    turn = [0]
 
     # comparators and partial passes (the default, "cat", is the headline path)
     conf_in, accumulate, passes = None, False, "fwd+bwd"
@@ -223,7 +225,8 @@ def main():
         conf_in = torch.from_numpy(synth.make_external_conf(wl.seed, agree)).to(dev)
     elif args.variant == "accumulate":       # dW += (gradient accumulation)
         accumulate = True
-        dW.zero_()
+        for t in dWs:
+            t.zero_()
     elif args.variant == "fwd":
         passes = "fwd"
     elif args.variant == "stats":            # stats-only forward = the teacher-confidence producer
@@ -250,6 +253,8 @@ def main():
     kd = args.variant == "kd"
 
     def step_kd():
+        turn[0] ^= 1
+        dH, dW = dHs[turn[0]], dWs[turn[0]]
         o = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws, out=out)
         b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, o["lse"], o["lse_t"], o["w"], valid_len=vl, dH=dH, dW=dW,
                            workspace=ws)
@@ -257,6 +262,8 @@ def main():
     def step():
         if kd:
             return step_kd()
+        turn[0] ^= 1
+        dH, dW = dHs[turn[0]], dWs[turn[0]]
         o = b.pard2_cat_fwd(desc, H, W, y, conf_in=conf_in, valid_len=vl, workspace=ws, out=out,
                             stats_only=(passes == "stats"))
         if passes == "fwd+bwd":
