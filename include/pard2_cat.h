@@ -58,6 +58,10 @@ typedef enum {
 enum { PARD2_BF16 = 0, PARD2_FP32 = 1 };                  /* storage of H, W, dH, dW; sums are fp32 */
 enum { PARD2_W_CAT = 0, PARD2_W_DECAY = 1, PARD2_W_UNIFORM = 2 };
 enum { PARD2_RED_MEAN_VALID = 0, PARD2_RED_SUM = 1 };
+/* descriptor flags.  PARD2_FLAG_DW_FP32: with bf16 storage, dW is an fp32 [V, d] buffer (written, or added to
+ * when accumulate_dW != 0, without intermediate rounding: the main-gradient buffer of gradient accumulation,
+ * Table 6's accumulation steps).  Ignored with fp32 storage, where dW is fp32 anyway. */
+enum { PARD2_FLAG_DW_FP32 = 1 };
 
 /* Problem descriptor (plain data, host memory). */
 typedef struct {
@@ -72,7 +76,7 @@ typedef struct {
   float beta;           /* coefficient of the CE term (Eq.12; 0.1 in Table 6, 1 gives Eq.11) */
   float gamma;          /* DECAY mode only, in (0, 1]                                        */
   int32_t ignore_index; /* a row whose target equals this carries no loss and no gradient    */
-  int32_t reserved;     /* set to 0                                                          */
+  int32_t flags;        /* 0, or PARD2_FLAG_DW_FP32                                           */
   int64_t ldH, ldW;     /* row strides of H and W in elements (>= d).  bf16: d, ldH, ldW must
                            be multiples of 8 and H, W 16-byte aligned                        */
 } pard2_cat_desc;
@@ -144,7 +148,8 @@ int pard2_cat_fwd(const pard2_cat_desc* desc, const void* H, const void* W, cons
  *   lse, w    [T]  as written by pard2_cat_fwd.
  *   grad_loss [1]  upstream gradient of the scalar loss, or NULL = 1.
  *   dH        [T,d] out, storage type desc->dtype; rows of invalid slots are zero.
- *   dW        [V,d] out (or += when accumulate_dW != 0), storage type desc->dtype.
+ *   dW        [V,d] out (or += when accumulate_dW != 0), storage type desc->dtype, or fp32 when
+ *                  desc->flags has PARD2_FLAG_DW_FP32.
  */
 int pard2_cat_bwd(const pard2_cat_desc* desc, const void* H, const void* W, const int32_t* y,
                   const int32_t* valid_len, const float* lse, const float* w,

@@ -15,6 +15,7 @@ from typing import Optional
 PARD2_BF16, PARD2_FP32 = 0, 1
 PARD2_W_CAT, PARD2_W_DECAY, PARD2_W_UNIFORM = 0, 1, 2
 PARD2_RED_MEAN_VALID, PARD2_RED_SUM = 0, 1
+PARD2_FLAG_DW_FP32 = 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libpard2cat.so")
 EXPORTS = ("pard2_cat_validate", "pard2_cat_workspace_bytes", "pard2_status_string", "pard2_cat_abi_version",
@@ -34,7 +35,7 @@ class Pard2Error(RuntimeError):
 class pard2_cat_desc(ctypes.Structure):
     _fields_ = [("T", c_int32), ("d", c_int32), ("V", c_int32), ("B", c_int32), ("K", c_int32),
                 ("dtype", c_int32), ("weight_mode", c_int32), ("reduction", c_int32),
-                ("beta", c_float), ("gamma", c_float), ("ignore_index", c_int32), ("reserved", c_int32),
+                ("beta", c_float), ("gamma", c_float), ("ignore_index", c_int32), ("flags", c_int32),
                 ("ldH", c_int64), ("ldW", c_int64)]
 
 
@@ -110,8 +111,8 @@ def _check(status: int, what: str) -> None:
 
 
 def make_desc(T, d, V, B, K, dtype, weight_mode=PARD2_W_CAT, reduction=PARD2_RED_MEAN_VALID, beta=0.1,
-              gamma=1.0, ignore_index=-100, ldH=None, ldW=None) -> pard2_cat_desc:
-    return pard2_cat_desc(T, d, V, B, K, dtype, weight_mode, reduction, beta, gamma, ignore_index, 0,
+              gamma=1.0, ignore_index=-100, ldH=None, ldW=None, flags=0) -> pard2_cat_desc:
+    return pard2_cat_desc(T, d, V, B, K, dtype, weight_mode, reduction, beta, gamma, ignore_index, flags,
                           d if ldH is None else ldH, d if ldW is None else ldW)
 
 
@@ -256,13 +257,14 @@ def pard2_cat_bwd(desc, H, W, y, lse, w, valid_len=None, grad_loss=None, dH=None
     _check_tensor(w, "w", torch.float32, desc.T, dev)
     _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
     _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
+    tdw = torch.float32 if desc.flags & PARD2_FLAG_DW_FP32 else td
     dH = torch.empty(desc.T, desc.d, dtype=td, device=dev) if dH is None else dH
     if dW is None:
         if accumulate_dW:
             raise Pard2Error("accumulate_dW needs an existing dW")
-        dW = torch.empty(desc.V, desc.d, dtype=td, device=dev)
+        dW = torch.empty(desc.V, desc.d, dtype=tdw, device=dev)
     _check_tensor(dH, "dH", td, desc.T * desc.d, dev)
-    _check_tensor(dW, "dW", td, desc.V * desc.d, dev)
+    _check_tensor(dW, "dW", tdw, desc.V * desc.d, dev)
     ws = alloc_workspace(desc, dev) if workspace is None else workspace
     wp, wn = _ws_args(ws)
     rc = lib().pard2_cat_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), _ptr(y), _ptr(valid_len), _ptr(lse), _ptr(w),
@@ -346,13 +348,14 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
         _check_tensor(t, name, torch.float32, desc.T, dev)
     _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
     _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
+    tdw = torch.float32 if desc.flags & PARD2_FLAG_DW_FP32 else td
     dH = torch.empty(desc.T, desc.d, dtype=td, device=dev) if dH is None else dH
     if dW is None:
         if accumulate_dW:
             raise Pard2Error("accumulate_dW needs an existing dW")
-        dW = torch.empty(desc.V, desc.d, dtype=td, device=dev)
+        dW = torch.empty(desc.V, desc.d, dtype=tdw, device=dev)
     _check_tensor(dH, "dH", td, desc.T * desc.d, dev)
-    _check_tensor(dW, "dW", td, desc.V * desc.d, dev)
+    _check_tensor(dW, "dW", tdw, desc.V * desc.d, dev)
     ws = alloc_kd_workspace(desc, te.d, dev) if workspace is None else workspace
     wp, wn = _ws_args(ws)
     rc = lib().pard2_cat_kd_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(valid_len),

@@ -183,6 +183,7 @@ const char* pard2_status_string(int s) {
 int pard2_cat_validate(const pard2_cat_desc* d) {
   if (!d) return PARD2_ERR_NULL;
   if (d->dtype != PARD2_BF16 && d->dtype != PARD2_FP32) return PARD2_ERR_DTYPE;
+  if (d->flags & ~PARD2_FLAG_DW_FP32) return PARD2_ERR_DTYPE;
   if (d->weight_mode < PARD2_W_CAT || d->weight_mode > PARD2_W_UNIFORM) return PARD2_ERR_DTYPE;
   if (d->reduction != PARD2_RED_MEAN_VALID && d->reduction != PARD2_RED_SUM) return PARD2_ERR_DTYPE;
   if (d->T <= 0 || d->d <= 0 || d->V <= 0 || d->B <= 0 || d->K <= 0) return PARD2_ERR_SHAPE;
@@ -287,7 +288,8 @@ int pard2_cat_bwd(const pard2_cat_desc* d, const void* H, const void* W, const i
     float* g = (float*)(ws + p.off_g);
     e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, d->beta, g, s);
     if (e != hipSuccess) return PARD2_ERR_LAUNCH;
-    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s);
+    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW,
+                        accumulate_dW | ((d->flags & PARD2_FLAG_DW_FP32) ? 2 : 0), ws, s);
   } else {
     const BwdPlanF32 p = plan_bwd_f32(d->T, d->d, d->V);
     float* g = (float*)(ws + p.off_g);
@@ -372,7 +374,8 @@ int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, cons
     float* g = (float*)(ws + p.off_g);
     e = launch_row_scale(w, y, valid_len, grad_loss, d->B, d->K, d->V, d->ignore_index, d->reduction, 1.f, g, s);
     if (e != hipSuccess) return PARD2_ERR_LAUNCH;
-    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
+    e = launch_bwd_bf16(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW,
+                        accumulate_dW | ((d->flags & PARD2_FLAG_DW_FP32) ? 2 : 0), ws, s, &kt);
   } else {
     const BwdPlanF32 p = plan_bwd_f32(d->T, d->d, d->V);
     float* g = (float*)(ws + p.off_g);

@@ -347,7 +347,7 @@ template <class C>
 __global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restrict__ H, int64_t ldH,
                                                          const __bf16* __restrict__ dZ, int64_t ldz, int T, int d,
                                                          int nvalid, int Kc, int nIt, int nVtc,
-                                                         __bf16* __restrict__ dWc, int accumulate) {
+                                                         __bf16* __restrict__ dWc, int accumulate, int dw_f32) {
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int it, vtl;
@@ -368,8 +368,14 @@ __global__ __launch_bounds__(C::NTHREADS) void dw_kernel(const __bf16* __restric
       for (int rq = 0; rq < 4; ++rq) {
         const int i = m0 + wp.m_of(mi, rq * 4);
         if (i >= d) continue;
-        bf16x4* p = reinterpret_cast<bf16x4*>(dWc + (int64_t)vr * d + i);
         f32x4 v = {acc[mi][ni][rq * 4], acc[mi][ni][rq * 4 + 1], acc[mi][ni][rq * 4 + 2], acc[mi][ni][rq * 4 + 3]};
+        if (dw_f32) {   // fp32 gradient buffer: no rounding between accumulation steps
+          f32x4* pf = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(dWc) + (int64_t)vr * d + i);
+          if (accumulate) v += *pf;
+          *pf = v;
+          continue;
+        }
+        bf16x4* p = reinterpret_cast<bf16x4*>(dWc + (int64_t)vr * d + i);
         if (accumulate) {
           const bf16x4 old = *p;
           v[0] += (float)old[0]; v[1] += (float)old[1]; v[2] += (float)old[2]; v[3] += (float)old[3];
@@ -456,6 +462,7 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
   if ((e = allow_lds(dw_kernel<Cfg>, Cfg::LDS_BYTES)) != hipSuccess) return e;
 
   const int nVt = ceil_div(V, Cfg::BM), nTt = ceil_div(T, Cfg::BN), nIt = ceil_div(d, Cfg::BM);
+  const int dw_f32 = (accumulate_dW & 2) != 0;   // bit 1: dW is an fp32 buffer
   for (int c = 0; c < p.nchunks; ++c) {
     const int vt0 = (int)((int64_t)c * nVt / p.nchunks), vt1 = (int)((int64_t)(c + 1) * nVt / p.nchunks);
     const int nVtc = vt1 - vt0;
@@ -488,7 +495,9 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     kt_end(KT_DH, s);
     kt_begin(KT_DW, s);
     hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
-                       ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc, (__bf16*)dW + (int64_t)v0 * d, accumulate_dW);
+                       ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc,
+                       dw_f32 ? (__bf16*)((float*)dW + (int64_t)v0 * d) : (__bf16*)dW + (int64_t)v0 * d,
+                       accumulate_dW & 1, dw_f32);
     kt_end(KT_DW, s);
   }
   return hipGetLastError();

@@ -79,6 +79,7 @@ struct BwdPlanBf16 {
   size_t off_g, off_dZ, off_dHacc, off_dHpart, total;
 };
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V);
+// accumulate_dW: bit 0 = add to dW, bit 1 = dW is an fp32 [V, d] buffer (else bf16).
 // The teacher side of the distillation term (Eq.12), when present: dZ then is
 // g_t (beta (q - 1[v = y_t]) + q - p) with p the teacher head's softmax.
 struct KdTeacher {

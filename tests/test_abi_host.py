@@ -60,6 +60,7 @@ def test_validate_and_workspace(b):
         (dict(dtype=7), -3),
         (dict(weight_mode=3), -3),
         (dict(reduction=2), -3),
+        (dict(flags=2), -3),                     # unknown descriptor flag
         (dict(beta=float("nan")), -6),
         (dict(weight_mode=b.PARD2_W_DECAY, gamma=0.0), -6),
         (dict(weight_mode=b.PARD2_W_DECAY, gamma=1.5), -6),

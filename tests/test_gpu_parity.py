@@ -329,3 +329,26 @@ def test_minimum_sizes(dtype):
         p = Hh.build_problem(B, K, d, V, dtype, seed=seed)
         _run_case(p, beta=1.0)
         _run_case(p, external=True)
+
+
+def test_fp32_dw_buffer_for_gradient_accumulation():
+    """PARD2_FLAG_DW_FP32: bf16 storage with an fp32 dW buffer; two accumulation steps add up without
+    intermediate rounding (two micro-batches of a gradient-accumulation step, Table 6)."""
+    p = Hh.build_problem(40, 8, 264, 3000, "bf16", seed=38, ragged_frac=0.2)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    desc = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0, flags=b.PARD2_FLAG_DW_FP32)
+    ref = Hh.oracle_forward(p, beta=1.0)
+    rb = O.cat_backward(p.head.H, None, p.y, ref["lse"], O.row_scale(ref["w"], 1.0, ref["n_valid"]), W64=p.W64)
+    out = b.pard2_cat_fwd(desc, H, W, y, valid_len=vl)
+    dH, dW = b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"], valid_len=vl)
+    assert dW.dtype == torch.float32 and dH.dtype == torch.bfloat16
+    Hh.check_grads(dH, dW, rb["dH"], rb["dW"], "bf16")
+    first = dW.clone()
+    b.pard2_cat_bwd(desc, H, W, y, out["lse"], out["w"], valid_len=vl, dW=dW, accumulate_dW=True)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, first + first)                   # fp32 sum of two identical fp32 results: exact
+    # and the bf16 buffer of the default path is this result rounded once
+    d16 = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_BF16, beta=1.0)
+    _, dW16 = b.pard2_cat_bwd(d16, H, W, y, out["lse"], out["w"], valid_len=vl)
+    assert torch.equal(dW16, first.to(torch.bfloat16))
