@@ -180,6 +180,7 @@ def main():
     ap.add_argument("--variant", default="cat",
                     help="cat (default) | decay0.8 | uniform | external | accumulate | fwd | stats | "
                          "kd (the Eq.12 token loss: beta CE + KD against a teacher head of width --teacher-d) | "
+                         "kd-deferred (same, loss and KL returned by the backward) | "
                          "inject (gated injection of 3 target features of width --teacher-d into the draft's input "
                          "embeddings, fwd+bwd: an adjacent step, not the loss)")
     ap.add_argument("--teacher-d", type=int, default=4096, help="hidden width of the teacher head (variant kd)")
@@ -231,7 +232,7 @@ def main():
         passes = "fwd"
     elif args.variant == "stats":            # stats-only forward = the teacher-confidence producer
         passes = "stats"
-    elif args.variant == "kd":               # weighted beta CE + KL(teacher || draft), two-head kernels
+    elif args.variant in ("kd", "kd-deferred"):   # weighted beta CE + KL(teacher || draft), two-head kernels
         # teacher recipe of synth.make_teacher, drawn on the device: draft operands extended by
         # independent columns, so that teacher logits = draft logits + noise of std ~2
         dt = args.teacher_d
@@ -250,14 +251,21 @@ def main():
         ws = b.alloc_kd_workspace(desc, dt, dev)
     elif args.variant != "cat":
         sys.exit(f"unknown variant {args.variant}")
-    kd = args.variant == "kd"
+    kd = args.variant in ("kd", "kd-deferred")
+    deferred = args.variant == "kd-deferred"   # forward without the cross term; KL and loss from the backward
+    kd_late = torch.empty(wl.T, dtype=torch.float32, device=dev)
+    loss_late = torch.empty(1, dtype=torch.float32, device=dev)
 
     def step_kd():
         turn[0] ^= 1
         dH, dW = dHs[turn[0]], dWs[turn[0]]
-        o = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws, out=out)
-        b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, o["lse"], o["lse_t"], o["w"], valid_len=vl, dH=dH, dW=dW,
-                           workspace=ws)
+        o = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws, out=out, defer_loss=deferred)
+        if deferred:
+            b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, o["lse"], o["lse_t"], o["w"], valid_len=vl, dH=dH, dW=dW,
+                               workspace=ws, logp_y=o["logp_y"], kd=kd_late, loss=loss_late)
+        else:
+            b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, o["lse"], o["lse_t"], o["w"], valid_len=vl, dH=dH, dW=dW,
+                               workspace=ws)
 
     def step():
         if kd:

@@ -189,6 +189,9 @@ size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* desc, int32_t teacher_
  *                  ignored rows use c = 1).
  *   lse_t     [T]  out: logsumexp of the teacher's rows (needed by the backward).
  *   kd        [T]  out or NULL: KL(p_t || q_t) per row.
+ * If loss and kd are BOTH NULL nothing asked for needs the two heads' logits side by side, and the
+ * call runs two single-head sweeps instead of the (slower per flop) two-head one: lse, lse_t, logp_y,
+ * w, argmax, accept_len, exp_len as usual; the loss of the step can then be had from the backward.
  * desc->beta must be >= 0 (else PARD2_ERR_HYPER). */
 int pard2_cat_kd_fwd(const pard2_cat_desc* desc, const void* H, const void* W,
                      const pard2_kd_teacher* teacher, const int32_t* y, const float* conf_in,
@@ -197,11 +200,16 @@ int pard2_cat_kd_fwd(const pard2_cat_desc* desc, const void* H, const void* W,
                      int32_t* dev_status, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of pard2_cat_kd_fwd's loss into the draft's H and W (weight and teacher constant).
- *   lse, lse_t, w  [T] as written by pard2_cat_kd_fwd.   Other arguments as pard2_cat_bwd. */
+ *   lse, lse_t, w  [T] as written by pard2_cat_kd_fwd.   Other arguments as pard2_cat_bwd.
+ *   kd        [T]  out or NULL, loss [1] out or NULL: the same values pard2_cat_kd_fwd returns,
+ *                  evaluated from the logits this call recomputes anyway (the cross term of the KL
+ *                  is summed per vocabulary tile and the tiles are added in a fixed order).
+ *   logp_y    [T]  as written by pard2_cat_kd_fwd; needed only when loss is requested, else NULL. */
 int pard2_cat_kd_bwd(const pard2_cat_desc* desc, const void* H, const void* W,
                      const pard2_kd_teacher* teacher, const int32_t* y, const int32_t* valid_len,
                      const float* lse, const float* lse_t, const float* w, const float* grad_loss,
                      void* dH, void* dW, int32_t accumulate_dW,
+                     const float* logp_y, float* kd, float* loss,
                      void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- Gated injection of target features into the draft's input embeddings (Sec.3.3) ---------

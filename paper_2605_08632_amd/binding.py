@@ -77,7 +77,8 @@ def lib() -> ctypes.CDLL:
     L.pard2_cat_kd_workspace_bytes.restype = c_size_t
     L.pard2_cat_kd_fwd.argtypes = [D, c_void_p, c_void_p, TE] + [c_void_p] * 13 + [c_void_p, c_size_t, c_void_p]
     L.pard2_cat_kd_fwd.restype = ctypes.c_int
-    L.pard2_cat_kd_bwd.argtypes = [D, c_void_p, c_void_p, TE] + [c_void_p] * 8 + [c_int32, c_void_p, c_size_t, c_void_p]
+    L.pard2_cat_kd_bwd.argtypes = ([D, c_void_p, c_void_p, TE] + [c_void_p] * 8 + [c_int32] + [c_void_p] * 3 +
+                                   [c_void_p, c_size_t, c_void_p])
     L.pard2_cat_kd_bwd.restype = ctypes.c_int
     L.pard2_inject_fwd.argtypes = [c_int32] * 4 + [c_void_p, POINTER(c_void_p), c_int64, c_void_p, c_void_p, c_void_p,
                                                  c_void_p]
@@ -296,9 +297,11 @@ def _teacher(desc, Ht, Wt, dev):
     return pard2_kd_teacher(Ht.data_ptr(), Wt.data_ptr(), Ht.stride(0), Wt.stride(0), Ht.shape[1], 0)
 
 
-def pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=None, valid_len=None, workspace=None, out=None):
+def pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=None, valid_len=None, workspace=None, out=None,
+                     defer_loss=False):
     """Forward of the weighted (beta CE + KD) loss.  Returns a dict of device tensors: loss, lse,
-    lse_t, logp_y, kd, w, argmax, accept_len, exp_len, dev_status."""
+    lse_t, logp_y, kd, w, argmax, accept_len, exp_len, dev_status.  With defer_loss the cheaper
+    forward without loss and kd runs (ask pard2_cat_kd_bwd for them)."""
     import torch
     dev = H.device
     td = _torch_dtype(desc)
@@ -316,25 +319,27 @@ def pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=None, valid_len=None, worksp
     o = {} if out is None else out
     f32 = dict(dtype=torch.float32, device=dev)
     i32 = dict(dtype=torch.int32, device=dev)
-    for k in ("lse", "lse_t", "logp_y", "kd", "w"):
+    for k in ("lse", "lse_t", "logp_y", "w") + (() if defer_loss else ("kd",)):
         o.setdefault(k, torch.empty(desc.T, **f32))
-    o.setdefault("loss", torch.empty(1, **f32))
+    if not defer_loss:
+        o.setdefault("loss", torch.empty(1, **f32))
     o.setdefault("argmax", torch.empty(desc.T, **i32))
     o.setdefault("accept_len", torch.empty(desc.B, **i32))
     o.setdefault("exp_len", torch.empty(desc.B, **f32))
     o.setdefault("dev_status", torch.empty(1, **i32))
     wp, wn = _ws_args(ws)
     rc = lib().pard2_cat_kd_fwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(conf_in),
-                                _ptr(valid_len), _ptr(o["loss"]), _ptr(o["lse"]), _ptr(o["lse_t"]), _ptr(o["logp_y"]),
-                                _ptr(o["kd"]), _ptr(o["w"]), _ptr(o["argmax"]), _ptr(o["accept_len"]),
+                                _ptr(valid_len), None if defer_loss else _ptr(o["loss"]), _ptr(o["lse"]),
+                                _ptr(o["lse_t"]), _ptr(o["logp_y"]), None if defer_loss else _ptr(o["kd"]), _ptr(o["w"]), _ptr(o["argmax"]), _ptr(o["accept_len"]),
                                 _ptr(o["exp_len"]), _ptr(o["dev_status"]), wp, wn, _stream())
     _check(rc, "pard2_cat_kd_fwd")
     return o
 
 
 def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_loss=None, dH=None, dW=None,
-                     accumulate_dW=False, workspace=None):
-    """Backward of pard2_cat_kd_fwd's loss into the draft's H and W.  Returns (dH, dW)."""
+                     accumulate_dW=False, workspace=None, logp_y=None, kd=None, loss=None):
+    """Backward of pard2_cat_kd_fwd's loss into the draft's H and W.  Returns (dH, dW).  Optional
+    outputs kd [T] and loss [1] (loss needs logp_y) receive the step's KL and loss."""
     import torch
     dev = H.device
     td = _torch_dtype(desc)
@@ -344,8 +349,9 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
         raise Pard2Error("H/W strides do not match the descriptor")
     te = _teacher(desc, Ht, Wt, dev)
     _check_tensor(y, "y", torch.int32, desc.T, dev)
-    for name, t in (("lse", lse), ("lse_t", lse_t), ("w", w)):
+    for name, t in (("lse", lse), ("lse_t", lse_t), ("w", w), ("logp_y", logp_y), ("kd", kd)):
         _check_tensor(t, name, torch.float32, desc.T, dev)
+    _check_tensor(loss, "loss", torch.float32, 1, dev)
     _check_tensor(valid_len, "valid_len", torch.int32, desc.B, dev)
     _check_tensor(grad_loss, "grad_loss", torch.float32, 1, dev)
     tdw = torch.float32 if desc.flags & PARD2_FLAG_DW_FP32 else td
@@ -360,7 +366,7 @@ def pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, lse, lse_t, w, valid_len=None, grad_
     wp, wn = _ws_args(ws)
     rc = lib().pard2_cat_kd_bwd(ctypes.byref(desc), _ptr(H), _ptr(W), ctypes.byref(te), _ptr(y), _ptr(valid_len),
                                 _ptr(lse), _ptr(lse_t), _ptr(w), _ptr(grad_loss), _ptr(dH), _ptr(dW),
-                                1 if accumulate_dW else 0, wp, wn, _stream())
+                                1 if accumulate_dW else 0, _ptr(logp_y), _ptr(kd), _ptr(loss), wp, wn, _stream())
     _check(rc, "pard2_cat_kd_bwd")
     return dH, dW
 

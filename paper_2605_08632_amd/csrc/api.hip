@@ -73,20 +73,32 @@ size_t bwd_bytes(const pard2_cat_desc* d) {
 
 // workspace of the two-head forward: both heads' partial statistics, per-row scratch
 struct KdFwdPlan {
-  int P;
-  size_t off_ms, off_idx, off_zy, off_ms_t, off_a_t, off_zy_t, off_tok, off_conf, off_hit, off_partials, total;
+  int P;    // vocabulary partials per row of the two-head sweep
+  int P1;   // ... of a single-head sweep (the forward without the cross term runs two of those)
+  size_t off_ms, off_idx, off_zy, off_ms_t, off_idx_t, off_a_t, off_zy_t, off_tok, off_conf, off_hit, off_partials,
+      total;
+};
+
+// workspace of the two-head backward beyond the single-head plan: per-row cross-term partials and the
+// per-row loss term, for a loss evaluated after the backward
+struct KdBwdExtra {
+  int nparts;
+  size_t off_part, off_tok, total;
 };
 
 KdFwdPlan plan_kd_fwd(const pard2_cat_desc* d) {
   KdFwdPlan p{};
   p.P = d->dtype == PARD2_BF16 ? kd_num_partials_bf16(d->T, d->V) : fwd_num_partials_f32(d->T, d->V);
+  p.P1 = d->dtype == PARD2_BF16 ? fwd_num_partials_bf16(d->T, d->V) : fwd_num_partials_f32(d->T, d->V);
+  const int pm = p.P > p.P1 ? p.P : p.P1;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o += align256(bytes); return at; };
-  p.off_ms = take((size_t)d->T * p.P * sizeof(float2));
-  p.off_idx = take((size_t)d->T * p.P * sizeof(int32_t));
+  p.off_ms = take((size_t)d->T * pm * sizeof(float2));
+  p.off_idx = take((size_t)d->T * pm * sizeof(int32_t));
   p.off_zy = take((size_t)d->T * 4);
-  p.off_ms_t = take((size_t)d->T * p.P * sizeof(float2));
-  p.off_a_t = take((size_t)d->T * p.P * sizeof(float));
+  p.off_ms_t = take((size_t)d->T * pm * sizeof(float2));
+  p.off_idx_t = take((size_t)d->T * pm * sizeof(int32_t));
+  p.off_a_t = take((size_t)d->T * pm * sizeof(float));
   p.off_zy_t = take((size_t)d->T * 4);
   p.off_tok = take((size_t)d->T * 4);
   p.off_conf = take((size_t)d->T * 4);
@@ -94,6 +106,18 @@ KdFwdPlan plan_kd_fwd(const pard2_cat_desc* d) {
   p.off_partials = take((size_t)scan_num_groups(d->B) * 2 * sizeof(double));
   p.total = o;
   return p;
+}
+
+KdBwdExtra plan_kd_bwd_extra(const pard2_cat_desc* d) {
+  KdBwdExtra x{};
+  x.nparts = d->dtype == PARD2_BF16 ? kd_num_row_parts_bf16(d->V) : kd_num_row_parts_f32(d->V);
+  size_t o = align256(bwd_bytes(d));
+  x.off_part = o;
+  o += align256((size_t)x.nparts * d->T * 4);
+  x.off_tok = o;
+  o += align256((size_t)d->T * 4);
+  x.total = o;
+  return x;
 }
 
 // descriptor + teacher checks shared by the two-head entry points (teacher pointers may be
@@ -302,7 +326,7 @@ int pard2_cat_bwd(const pard2_cat_desc* d, const void* H, const void* W, const i
 
 size_t pard2_cat_kd_workspace_bytes(const pard2_cat_desc* d, int32_t teacher_d) {
   if (validate_kd(d, teacher_d, teacher_d, teacher_d) != PARD2_OK) return 0;
-  const size_t f = plan_kd_fwd(d).total, b = bwd_bytes(d);
+  const size_t f = plan_kd_fwd(d).total, b = plan_kd_bwd_extra(d).total;
   return f > b ? f : b;
 }
 
@@ -329,9 +353,40 @@ int pard2_cat_kd_fwd(const pard2_cat_desc* d, const void* H, const void* W, cons
   float* tok = (float*)(ws + p.off_tok);
   float* conf = (float*)(ws + p.off_conf);
   int32_t* hit = (int32_t*)(ws + p.off_hit);
-  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, nullptr, d->beta};
+  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, nullptr, d->beta, nullptr};
 
   if (dev_status) hipLaunchKernelGGL(set_i32_kernel, dim3(1), dim3(1), 0, s, dev_status, 0);
+  if (!loss && !kd) {
+    // Nothing asked for needs both heads' logits at the same (token, id): two single-head sweeps at the
+    // single-head kernels' larger tile.  The cross term of the KL can be had from the backward instead.
+    StatsOut sd{st.draft.ms, st.draft.idx, st.draft.zy, p.P1};
+    StatsOut stt{st.ms_t, (int32_t*)(ws + p.off_idx_t), st.zy_t, p.P1};
+    hipError_t e1, e2;
+    if (d->dtype == PARD2_BF16) {
+      e1 = launch_fwd_stats_bf16(te->H, te->ldH, te->W, te->ldW, y, d->T, te->d, d->V, stt, s);
+      e2 = launch_fwd_stats_bf16(H, d->ldH, W, d->ldW, y, d->T, d->d, d->V, sd, s);
+    } else {
+      e1 = launch_fwd_stats_f32(te->H, te->ldH, te->W, te->ldW, y, d->T, te->d, d->V, stt, s);
+      e2 = launch_fwd_stats_f32(H, d->ldH, W, d->ldW, y, d->T, d->d, d->V, sd, s);
+    }
+    if (e1 != hipSuccess || e2 != hipSuccess) return PARD2_ERR_LAUNCH;
+    // teacher: lse_t and the confidence (given, or its own p(y), Eq.9); tok serves as scratch for log p(y)
+    if (launch_combine(stt, y, conf_in, d->T, d->V, d->ignore_index, lse_t, tok, nullptr, conf, nullptr, dev_status,
+                       s) != hipSuccess)
+      return PARD2_ERR_LAUNCH;
+    if (launch_combine(sd, y, nullptr, d->T, d->V, d->ignore_index, lse, logp_y, argmax, nullptr, hit, dev_status, s) !=
+        hipSuccess)
+      return PARD2_ERR_LAUNCH;
+    if (w || accept_len || exp_len) {
+      ScanArgs a{};
+      a.conf = conf; a.y = y; a.valid_len = valid_len; a.hit = hit;
+      a.w = w; a.exp_len = exp_len; a.accept_len = accept_len;
+      a.B = d->B; a.K = d->K; a.V = d->V; a.ignore_index = d->ignore_index;
+      a.weight_mode = d->weight_mode; a.reduction = d->reduction; a.beta = 1.f; a.gamma = d->gamma;
+      if (launch_scan(a, s) != hipSuccess) return PARD2_ERR_LAUNCH;
+    }
+    return PARD2_OK;
+  }
   const hipError_t e = d->dtype == PARD2_BF16 ? launch_kd_stats_bf16(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s)
                                               : launch_kd_stats_f32(H, d->ldH, W, d->ldW, kt, y, d->T, d->d, d->V, st, s);
   if (e != hipSuccess) return PARD2_ERR_LAUNCH;
@@ -353,20 +408,23 @@ int pard2_cat_kd_fwd(const pard2_cat_desc* d, const void* H, const void* W, cons
 
 int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, const pard2_kd_teacher* te,
                      const int32_t* y, const int32_t* valid_len, const float* lse, const float* lse_t, const float* w,
-                     const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW, void* workspace,
-                     size_t workspace_bytes, void* stream) {
+                     const float* grad_loss, void* dH, void* dW, int32_t accumulate_dW, const float* logp_y,
+                     float* kd, float* loss, void* workspace, size_t workspace_bytes, void* stream) {
   if (!d || !te) return PARD2_ERR_NULL;
   int rc = validate_kd(d, te->d, te->ldH, te->ldW);
   if (rc != PARD2_OK) return rc;
   if (!H || !W || !te->H || !te->W || !y || !lse || !lse_t || !w || !dH || !dW) return PARD2_ERR_NULL;
+  if (loss && !logp_y) return PARD2_ERR_NULL;
   if (d->dtype == PARD2_BF16 && (misaligned16(H) || misaligned16(W) || misaligned16(te->H) || misaligned16(te->W) ||
                                  misaligned16(dH) || misaligned16(dW)))
     return PARD2_ERR_SHAPE;
-  if ((rc = check_workspace(workspace, workspace_bytes, bwd_bytes(d))) != PARD2_OK) return rc;
+  const KdBwdExtra x = plan_kd_bwd_extra(d);
+  if ((rc = check_workspace(workspace, workspace_bytes, x.total)) != PARD2_OK) return rc;
   if ((rc = check_arch()) != PARD2_OK) return rc;
   hipStream_t s = (hipStream_t)stream;
   char* ws = (char*)workspace;
-  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, lse_t, d->beta};
+  float* kd_part = (kd || loss) ? (float*)(ws + x.off_part) : nullptr;
+  const KdTeacher kt{te->H, te->W, te->ldH, te->ldW, te->d, lse_t, d->beta, kd_part};
   // g_t = grad_loss w_t / N: beta sits inside the bracket of Eq.12
   hipError_t e;
   if (d->dtype == PARD2_BF16) {
@@ -383,7 +441,16 @@ int pard2_cat_kd_bwd(const pard2_cat_desc* d, const void* H, const void* W, cons
     if (e != hipSuccess) return PARD2_ERR_LAUNCH;
     e = launch_bwd_f32(p, H, d->ldH, W, d->ldW, y, lse, g, d->T, d->d, d->V, dH, dW, accumulate_dW, ws, s, &kt);
   }
-  return e == hipSuccess ? PARD2_OK : PARD2_ERR_LAUNCH;
+  if (e != hipSuccess) return PARD2_ERR_LAUNCH;
+  if (kd_part) {   // the loss of this step, evaluated from what the backward's recompute saw
+    float* tok = (float*)(ws + x.off_tok);
+    if (launch_kd_finish(kd_part, x.nparts, lse, lse_t, logp_y, y, d->beta, d->T, d->V, kd, loss ? tok : nullptr, s) !=
+        hipSuccess)
+      return PARD2_ERR_LAUNCH;
+    if (loss && launch_weighted_loss(w, tok, y, valid_len, d->B, d->K, d->V, d->reduction, loss, s) != hipSuccess)
+      return PARD2_ERR_LAUNCH;
+  }
+  return PARD2_OK;
 }
 
 static int validate_inject(int32_t T, int32_t d, int32_t dt, int32_t F, int64_t ldX) {

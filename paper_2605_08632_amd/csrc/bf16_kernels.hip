@@ -470,7 +470,7 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     const int Kc = nVtc * Cfg::BM;                  // padded chunk width (dZ columns written)
     const int nvalid = (V - v0 < Kc) ? V - v0 : Kc; // vocabulary rows that exist in the chunk
     if (kd) {   // distillation term present: the two-head recompute forms dZ
-      if ((e = launch_kd_dz_bf16(H, ldH, W, ldW, *kd, y, lse, g, T, d, V, v0, Kc, dZ, p.Vc, s)) != hipSuccess) return e;
+      if ((e = launch_kd_dz_bf16(H, ldH, W, ldW, *kd, y, lse, g, T, d, V, v0, Kc, dZ, p.Vc, kd->kd_part, s)) != hipSuccess) return e;
     } else {
       kt_begin(KT_DZ, s);
       hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,

@@ -225,7 +225,15 @@ struct KdDzEpi {
   float* dZ;
   int64_t ldz;
   int v0;
+  float* kd_part;   // or null: [vocabulary tile][T] per-row sums of p (zT - zD)
   __device__ void operator()(int m0, int n0, int M, int N, float (*ZT)[FT + 1], float (*ZD)[FT + 1]) const {
+    if (kd_part && threadIdx.x < FT && m0 + (int)threadIdx.x < M) {
+      const int r = threadIdx.x, t = m0 + r;
+      const int ncol = min(FT, N - n0);
+      float a = 0.f;
+      for (int j = 0; j < ncol; ++j) a += expf(ZT[r][j] - lse_t[t]) * (ZT[r][j] - ZD[r][j]);
+      kd_part[(int64_t)(v0 / FT + blockIdx.y) * M + t] = a;
+    }
     for (int e = threadIdx.x; e < FT * FT; e += 256) {
       const int r = e / FT, j = e % FT;
       const int t = m0 + r, c = n0 + j;
@@ -237,6 +245,8 @@ struct KdDzEpi {
 };
 
 static int cdiv(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+int kd_num_row_parts_f32(int V) { return cdiv(V, FT); }
 
 int fwd_num_partials_f32(int T, int V) {
   (void)T;
@@ -288,7 +298,7 @@ hipError_t launch_bwd_f32(const BwdPlanF32& p, const void* H_, int64_t ldH, cons
     const int nc = (int)((V - v0 < p.Vc) ? V - v0 : p.Vc);
     // dZ chunk [T][nc]: z = H W[v0..]^T
     if (kd) {
-      KdDzEpi dz{y, lse, kd->lse, g, kd->beta, dZ, p.Vc, v0};
+      KdDzEpi dz{y, lse, kd->lse, g, kd->beta, dZ, p.Vc, v0, kd->kd_part};
       hipLaunchKernelGGL(gemm2_f32_kernel<KdDzEpi>, dim3(cdiv(T, FT), cdiv(nc, FT)), dim3(256), 0, s,
                          (const float*)kd->H, kd->ldH, (const float*)kd->W + (int64_t)v0 * kd->ldW, kd->ldW, kd->d, H,
                          ldH, W + (int64_t)v0 * ldW, ldW, d, T, nc, dz);

@@ -228,9 +228,11 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
     const __bf16* __restrict__ Ht, int64_t ldHt, const __bf16* __restrict__ Wt, int64_t ldWt,
     const int32_t* __restrict__ y, const float* __restrict__ lse, const float* __restrict__ lse_t,
     const float* __restrict__ g, float beta, int T, int d, int dt, int V, int nTt, int vt0, int nVtc,
-    __bf16* __restrict__ dZ, int64_t ldz) {
+    __bf16* __restrict__ dZ, int64_t ldz, float* __restrict__ kd_part) {
   extern __shared__ __align__(16) char smem[];
   constexpr int KD_DZ_PITCH = kd_dz_pitch<C>();
+  static_assert(C::BN * KD_DZ_PITCH + C::WGM * C::BN * 4 <= kd_dz_lds_bytes<C>(), "row sums sit behind the staged tile");
+  float* sh_a = reinterpret_cast<float*>(smem + C::BN * KD_DZ_PITCH);   // [WGM][BN] per-row sums of the tile
   const WavePos<C> wp;
   int tt, vtl;
   banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, 8, tt, vtl);
@@ -257,6 +259,7 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
       const float nlT = row ? -lse_t[t] * L2E : -INFINITY;
       const int yv = row ? y[t] : -1;
       const float gq = gt * (1.f + beta), gy = gt * beta;
+      float arow = 0.f;
       if (ragged) {
 #pragma unroll
         for (int mi = 0; mi < C::MI; ++mi)
@@ -277,9 +280,15 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
             const float q = __builtin_amdgcn_exp2f(__builtin_fmaf(accD[mi][ni][rq * 4 + j], L2E, nlD));
             const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(accT[mi][ni][rq * 4 + j], L2E, nlT));
             pk[j] = (__bf16)(gq * q - gt * p);
+            // cross term of KL(p || q): p (zT - zD); p == 0 covers ids past V and rows past T
+            if (kd_part) arow += (p > 0.f) ? p * (accT[mi][ni][rq * 4 + j] - accD[mi][ni][rq * 4 + j]) : 0.f;
           }
           *reinterpret_cast<bf16x4*>(smem + tl * KD_DZ_PITCH + wp.m_of(mi, rq * 4) * 2) = pk;
         }
+      if (kd_part) {   // the two half-wavefronts hold interleaved ids of the same rows
+        arow += __shfl_xor(arow, 32);
+        if (wp.lane < 32) sh_a[wp.wm * C::BN + tl] = arow;
+      }
       // the target element carries the extra -beta g
       const int rel = yv - (m0 + wp.wm * C::WTM);
       if (rel >= 0 && rel < C::WTM) {
@@ -310,6 +319,14 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
       *reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8) = v;
     }
   }
+  // per-row sum_v p (zT - zD) over this tile's ids -> kd_part[tile][t] (tiles past V write nothing)
+  if (kd_part && live) {
+    for (int n = threadIdx.x; n < C::BN; n += C::NTHREADS) {
+      float a = sh_a[n];
+      for (int w = 1; w < C::WGM; ++w) a += sh_a[w * C::BN + n];
+      if (n0 + n < T) kd_part[(int64_t)(vt0 + vtl) * T + n0 + n] = a;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------
@@ -322,6 +339,8 @@ static hipError_t allow_lds(K kernel, int bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                              bytes);
 }
+
+int kd_num_row_parts_bf16(int V) { return ceil_div(V, KdCfg::BM); }
 
 int kd_num_partials_bf16(int T, int V) {
   const int nTt = ceil_div(T, KdCfg::BN), nVt = ceil_div(V, KdCfg::BM);
@@ -346,7 +365,7 @@ hipError_t launch_kd_stats_bf16(const void* H, int64_t ldH, const void* W, int64
 
 hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& te,
                              const int32_t* y, const float* lse, const float* g, int T, int d, int V, int v0, int Kc,
-                             void* dZ, int64_t ldz, hipStream_t s) {
+                             void* dZ, int64_t ldz, float* kd_part, hipStream_t s) {
   if (v0 % KdCfg::BM != 0 || Kc % KdCfg::BM != 0 || v0 >= V) return hipErrorInvalidValue;
   constexpr int LDS = kd_dz_lds_bytes<KdCfg>();
   auto k = kd_dz_kernel<KdCfg>;
@@ -356,7 +375,7 @@ hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t 
   kt_begin(KT_KD_DZ, s);
   hipLaunchKernelGGL(k, dim3(nTt * nVtc), dim3(KdCfg::NTHREADS), LDS, s, (const __bf16*)H, ldH, (const __bf16*)W, ldW,
                      (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, lse, te.lse, g, te.beta, T, d, te.d,
-                     V, nTt, v0 / KdCfg::BM, nVtc, (__bf16*)dZ, ldz);
+                     V, nTt, v0 / KdCfg::BM, nVtc, (__bf16*)dZ, ldz, kd_part);
   kt_end(KT_KD_DZ, s);
   return hipGetLastError();
 }

@@ -89,6 +89,9 @@ struct KdTeacher {
   int d;
   const float* lse;    // [T] logsumexp of the teacher's rows
   float beta;
+  // backward only, or null: [row parts][T] per-row partial sums of p (zT - zD), one part per vocabulary
+  // tile of the two-head dZ kernel (kd_num_row_parts_* parts), for a loss evaluated after the backward
+  float* kd_part;
 };
 hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, const void* W, int64_t ldW,
                            const int32_t* y, const float* lse, const float* g, int T, int d, int V,
@@ -117,7 +120,16 @@ hipError_t launch_kd_combine(KdStatsOut st, const int32_t* y, const float* conf_
 // dZ of one vocabulary chunk (tiles of kd_dz_tile() ids starting at id v0, Kc ids wide) into dZ[t][v - v0].
 hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t ldW, const KdTeacher& teacher,
                              const int32_t* y, const float* lse, const float* g, int T, int d, int V, int v0, int Kc,
-                             void* dZ, int64_t ldz, hipStream_t s);
+                             void* dZ, int64_t ldz, float* kd_part, hipStream_t s);
+int kd_num_row_parts_bf16(int V);
+int kd_num_row_parts_f32(int V);
+// kd[t] = sum over parts of kd_part[part][t] - lse_t[t] + lse[t]; tok[t] = beta log q(y) - kd (0 without target)
+hipError_t launch_kd_finish(const float* kd_part, int nparts, const float* lse, const float* lse_t,
+                            const float* logp_y, const int32_t* y, float beta, int T, int V, float* kd, float* tok,
+                            hipStream_t s);
+// loss = (1/N) sum over valid rows of w[t] * (-tok[t])  (N = valid rows, or 1 for the SUM reduction)
+hipError_t launch_weighted_loss(const float* w, const float* tok, const int32_t* y, const int32_t* valid_len, int B,
+                                int K, int V, int reduction, float* loss, hipStream_t s);
 
 // ---- backward, fp32 storage
 struct BwdPlanF32 {

@@ -114,6 +114,73 @@ hipError_t launch_kd_combine(KdStatsOut st, const int32_t* y, const float* conf_
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- loss after the backward (two heads)
+// The two-head dZ kernel leaves, per vocabulary tile, each row's sum_v p (zT - zD); summed over the
+// tiles in a fixed order that is the cross term of KL(p || q) = sum - lse_t + lse.
+__global__ __launch_bounds__(256) void kd_finish_kernel(const float* __restrict__ kd_part, int nparts,
+                                                        const float* __restrict__ lse, const float* __restrict__ lse_t,
+                                                        const float* __restrict__ logp_y, const int32_t* __restrict__ y,
+                                                        float beta, int T, int V, float* __restrict__ kd,
+                                                        float* __restrict__ tok) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= T) return;
+  float a = 0.f;
+  for (int j = 0; j < nparts; ++j) a += kd_part[(int64_t)j * T + t];
+  const float kl = a - lse_t[t] + lse[t];
+  if (kd) kd[t] = kl;
+  const int yv = y[t];
+  if (tok) tok[t] = (yv >= 0 && yv < V) ? beta * logp_y[t] - kl : 0.f;
+}
+
+hipError_t launch_kd_finish(const float* kd_part, int nparts, const float* lse, const float* lse_t,
+                            const float* logp_y, const int32_t* y, float beta, int T, int V, float* kd, float* tok,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(kd_finish_kernel, dim3((T + 255) / 256), dim3(256), 0, s, kd_part, nparts, lse, lse_t, logp_y, y,
+                     beta, T, V, kd, tok);
+  return hipGetLastError();
+}
+
+// loss = (1/N) sum_t w_t (-tok_t) over valid rows, one workgroup, fixed-order fp64 tree (reproducible).
+__global__ __launch_bounds__(1024) void weighted_loss_kernel(const float* __restrict__ w, const float* __restrict__ tok,
+                                                             const int32_t* __restrict__ y,
+                                                             const int32_t* __restrict__ valid_len, int B, int K, int V,
+                                                             int reduction, float* __restrict__ loss) {
+  __shared__ double sh_sum[1024];
+  __shared__ int sh_cnt[1024];
+  const int64_t T = (int64_t)B * K;
+  double sum = 0.0;
+  int cnt = 0;
+  for (int64_t t = threadIdx.x; t < T; t += blockDim.x) {
+    const int b = (int)(t / K), k = (int)(t % K);
+    const int Kb = valid_len ? valid_len[b] : K;
+    const int yv = y[t];
+    if (k < Kb && yv >= 0 && yv < V) {
+      sum += (double)w[t] * (double)(-tok[t]);
+      ++cnt;
+    }
+  }
+  sh_sum[threadIdx.x] = sum;
+  sh_cnt[threadIdx.x] = cnt;
+  __syncthreads();
+  for (int s = 512; s > 0; s >>= 1) {
+    if ((int)threadIdx.x < s) {
+      sh_sum[threadIdx.x] += sh_sum[threadIdx.x + s];
+      sh_cnt[threadIdx.x] += sh_cnt[threadIdx.x + s];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double l = reduction == 0 ? (sh_cnt[0] > 0 ? sh_sum[0] / sh_cnt[0] : 0.0) : sh_sum[0];
+    *loss = (float)l;
+  }
+}
+
+hipError_t launch_weighted_loss(const float* w, const float* tok, const int32_t* y, const int32_t* valid_len, int B,
+                                int K, int V, int reduction, float* loss, hipStream_t s) {
+  hipLaunchKernelGGL(weighted_loss_kernel, dim3(1), dim3(1024), 0, s, w, tok, y, valid_len, B, K, V, reduction, loss);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- per-block scan
 // One thread per draft block walks its K slots left to right:
 //   s_0 = 1, s_k = s_{k-1} * c_{k-1}   (Eq.10), or gamma^k / 1 for the comparators,

@@ -117,7 +117,8 @@ def test_kd_entry_points_validate_on_the_host(b):
     assert L.pard2_cat_kd_fwd(ctypes.byref(desc), one, one, ctypes.byref(te), *args, None, 0, None) == -4
     bad = b.pard2_kd_teacher(one, one, 64, 128, 128, 0)              # stride below the teacher's width
     assert L.pard2_cat_kd_fwd(ctypes.byref(desc), one, one, ctypes.byref(bad), *args, None, 0, None) == -2
-    assert L.pard2_cat_kd_bwd(ctypes.byref(desc), one, one, ctypes.byref(te), *([None] * 8), 0, None, 0, None) == -1
+    assert L.pard2_cat_kd_bwd(ctypes.byref(desc), one, one, ctypes.byref(te), *([None] * 8), 0, None, None, None,
+                              None, 0, None) == -1
 
 
 def test_inject_entry_points_validate_on_the_host(b):

@@ -150,3 +150,20 @@ def test_fullsize_kd_c2_teacher4096():
     rhs = (dH64 * H.double()).sum().item()
     assert abs(lhs - rhs) <= 1e-2 * max(abs(lhs), abs(rhs)), (lhs, rhs)
     print(f"[fullsize kd] identities ok: <dW,W> {lhs:.6e} <dH,H> {rhs:.6e}", flush=True)
+
+    # deferred loss (the configuration `bench.py --variant kd-deferred` times): forward without the cross
+    # term, KL per row and loss from the backward
+    out2 = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, valid_len=vl, workspace=ws, defer_loss=True)
+    kd2 = torch.empty(p.T, dtype=torch.float32, device=H.device)
+    loss2 = torch.empty(1, dtype=torch.float32, device=H.device)
+    dH2, dW2 = b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, out2["lse"], out2["lse_t"], out2["w"], valid_len=vl,
+                                  workspace=ws, logp_y=out2["logp_y"], kd=kd2, loss=loss2)
+    torch.cuda.synchronize()
+    g2 = Hh.check_forward(out2, ref, p, stats_only=True)
+    np.testing.assert_allclose(g2["lse_t"], ref["lse_t"], rtol=tol["stat"], atol=tol["stat"])
+    np.testing.assert_allclose(kd2.cpu().numpy(), ref["kd"], rtol=3 * tol["stat"], atol=3 * tol["stat"])
+    assert abs(loss2.item() - ref["loss"]) <= tol["loss"] * abs(ref["loss"])
+    eH = np.max(np.abs(dH2[torch.from_numpy(rows).to(H.device)].float().cpu().numpy() - rb["dH"])) / np.max(np.abs(rb["dH"]))
+    eW = np.max(np.abs(dW2[torch.from_numpy(vrows).to(H.device)].float().cpu().numpy() - rb["dW"])) / np.max(np.abs(rb["dW"]))
+    assert eH <= tol["grad"] and eW <= tol["grad"]
+    print(f"[fullsize kd] deferred loss ok: loss {loss2.item():.6f}, dH {eH:.2e}, dW {eW:.2e}", flush=True)

@@ -79,6 +79,24 @@ def run_kd_case(p, beta=0.1, mode=O.W_CAT, gamma=1.0, reduction=O.RED_MEAN_VALID
     inv = ~O.valid_mask(p.y, p.B, p.K, p.valid_len)
     if inv.any():
         assert not dH.float().cpu().numpy()[inv].any()
+
+    # deferred loss: the forward without the cross term (two single-head sweeps), then a backward that also
+    # returns KL per row and the loss from the logits it recomputes
+    out2 = b.pard2_cat_kd_fwd(desc, H, W, Ht, Wt, y, conf_in=conf if external else None, valid_len=vl, workspace=ws,
+                              defer_loss=True)
+    assert "loss" not in out2 and "kd" not in out2
+    g2 = Hh.check_forward(out2, ref, p, stats_only=True)
+    np.testing.assert_allclose(g2["lse_t"], ref["lse_t"], rtol=tol["stat"], atol=tol["stat"])
+    np.testing.assert_allclose(g2["w"], ref["w"], rtol=10 * tol["stat"], atol=1e-30)
+    kd2 = torch.empty(p.T, dtype=torch.float32, device=H.device)
+    loss2 = torch.empty(1, dtype=torch.float32, device=H.device)
+    dH2, dW2 = b.pard2_cat_kd_bwd(desc, H, W, Ht, Wt, y, out2["lse"], out2["lse_t"], out2["w"], valid_len=vl,
+                                  grad_loss=gl, dW=None if dW0 is None else dW0.clone(), accumulate_dW=accumulate,
+                                  workspace=ws, logp_y=out2["logp_y"], kd=kd2, loss=loss2)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(kd2.cpu().numpy(), ref["kd"], rtol=3 * tol["stat"], atol=3 * tol["stat"])
+    assert abs(loss2.item() - ref["loss"]) <= tol["loss"] * abs(ref["loss"]) + 1e-9, (loss2.item(), ref["loss"])
+    Hh.check_grads(dH2, dW2, rb["dH"], ref_dW, p.dtype)
     return eH, eW, out, (dH, dW)
 
 
