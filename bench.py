@@ -33,6 +33,9 @@ MEASURED_TRAFFIC = {
         "dz_kernel": (839.5 * MIB, 250.5 * MIB),
         "dh_kernel": (808.0 * MIB, 69.3 * MIB),
         "dw_kernel": (820.2 * MIB, 64.7 * MIB),
+        # variant kd, teacher width 4096 (profiles/c2_llama1b_kd_teacher4096_kernel_trace.md)
+        "kd_stats_kernel": (34700.4 * MIB, 4.4 * MIB),
+        "kd_dz_kernel": (3830.4 * MIB, 250.5 * MIB),
     },
 }
 
@@ -338,9 +341,13 @@ def main():
     flops_kernel_per_launch = 2.0 * wl.T * wl.V * width * args.steps / max(k_n, 1)
     achieved = flops_kernel_per_launch / (k_ms / max(k_n, 1) * 1e-3) / 1e12
     tr = MEASURED_TRAFFIC.get(wl.name, {}).get(b.KERNEL_NAMES[k])
+    if b.KERNEL_NAMES[k].startswith("kd_") and args.teacher_d != 4096:
+        tr = None                                # the stored counters are for the 4096-wide teacher
     traffic = None if tr is None else tr[0] + tr[1]           # bytes per launch
     traffic_detail = None if tr is None else {"fetch_bytes": tr[0], "write_bytes": tr[1],
-                                              "source": "profiles/c2_llama1b_hbm_traffic.md"}
+                                              "source": "profiles/c2_llama1b_kd_teacher4096_kernel_trace.md"
+                                              if b.KERNEL_NAMES[k].startswith("kd_") else
+                                              "profiles/c2_llama1b_hbm_traffic.md"}
     res = {
         "metric": "CAT loss fwd+bwd tokens/s and % bf16 MFMA peak, d=2048 V=128256 T=8192",
         "value": n_valid / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
