@@ -161,3 +161,26 @@ def test_header_is_plain_c_and_links(b, tmp_path):
     assert r.returncode == 0, r.stderr
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "abi_host_check ok" in r.stdout, r.stdout + r.stderr
+
+
+def test_product_path_is_independent_of_the_oracle():
+    """Nothing under the package (Python or HIP sources) imports, includes or names a file of oracle/,
+    and the oracle imports nothing from the package; bench.py touches the oracle in its CPU-baseline
+    leg only."""
+    pkg = os.path.join(ROOT, "paper_2605_08632_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath or "__pycache__" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, f), encoding="utf-8").read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), f
+                assert "cat_oracle" not in text and "inject_oracle" not in text and "oracle/" not in text, f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2605_08632_amd" not in open(os.path.join(ROOT, "oracle", f), encoding="utf-8").read(), f
+    bench = open(os.path.join(ROOT, "bench.py"), encoding="utf-8").read()
+    uses = [m.start() for m in re.finditer(r"from oracle import", bench)]
+    start = bench.index("def cpu_baseline")
+    end = bench.index("\ndef ", start + 1)
+    assert len(uses) == 1 and start < uses[0] < end
