@@ -19,6 +19,10 @@ namespace pard2 {
 #endif
 using Cfg = TileCfg<PARD2_TILE>;
 // token tiles per band of the tile rasterisation (how many token tiles share a vocabulary tile inside an XCD)
+// vocabulary tiles (of 256 ids) per chunk of the split-V backward
+#ifndef PARD2_CHUNK_TILES
+#define PARD2_CHUNK_TILES 64
+#endif
 #ifndef PARD2_BAND_FWD
 #define PARD2_BAND_FWD 8
 #endif
@@ -435,7 +439,7 @@ static std::pair<int, int> dh_k_slices(int T, int d, int Kc) {
 BwdPlanBf16 plan_bwd_bf16(int T, int d, int V) {
   BwdPlanBf16 p{};
   const int nVt = ceil_div(V, Cfg::BM);
-  const int max_tiles = 64;   // vocabulary tiles per chunk (Vc <= 16384)
+  const int max_tiles = PARD2_CHUNK_TILES;   // vocabulary tiles per chunk (Vc <= 16384 by default)
   p.nchunks = ceil_div(nVt, max_tiles);
   p.Vc = (int64_t)ceil_div(nVt, p.nchunks) * Cfg::BM;
   size_t o = 0;
