@@ -201,7 +201,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(the path shards by draft blocks; see DESIGN.md)")
+                 "(the path would shard by draft blocks, with one all-reduce of two scalars and the usual dW reduction)")
 
     import torch
     from paper_2605_08632_amd import binding as b, synth
