@@ -18,6 +18,10 @@ namespace pard2 {
 #define PARD2_KD_TILE 128, 256, 2, 4
 #endif
 using KdCfg = TileCfg<PARD2_KD_TILE>;
+// token tiles per band of the tile rasterisation
+#ifndef PARD2_KD_BAND
+#define PARD2_KD_BAND 8
+#endif
 
 // Teacher-side running statistics of a row over a set of ids: max, s = sum exp(zT - max) and
 // a = sum exp(zT - max) (zT - zD); at the end  sum_v p(v) (zT - zD)(v) = a / s.
@@ -50,7 +54,7 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_stats_kernel(
   extern __shared__ __align__(16) char smem[];
   const WavePos<C> wp;
   int tt, sp;
-  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, 8, tt, sp);
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nsplit, PARD2_KD_BAND, tt, sp);
   const int n0 = tt * C::BN;
   const int vt_begin = (int)((int64_t)sp * nVt / nsplit), vt_end = (int)((int64_t)(sp + 1) * nVt / nsplit);
 
@@ -235,7 +239,7 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
   float* sh_a = reinterpret_cast<float*>(smem + C::BN * KD_DZ_PITCH);   // [WGM][BN] per-row sums of the tile
   const WavePos<C> wp;
   int tt, vtl;
-  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, 8, tt, vtl);
+  banded_tile(xcd_contiguous_id(blockIdx.x, gridDim.x), nTt, nVtc, PARD2_KD_BAND, tt, vtl);
   const int n0 = tt * C::BN, m0 = (vt0 + vtl) * C::BM, c0 = vtl * C::BM;
   const bool live = m0 < V;   // workgroup-uniform
 
