@@ -242,7 +242,7 @@ int pard2_inject_bwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* dE
                      int32_t accumulate_dP, void* stream);
 
 /* Measurement aid (not part of the method).  pard2_cat_kernel_timing(1) makes every later
- * launch of the contraction kernels record a pair of HIP events on its stream;
+ * launch of the contraction kernels carry a pair of HIP events on its own dispatch;
  * pard2_cat_kernel_timing(0) switches it off; either call forgets earlier records.
  * pard2_cat_kernel_timing_read waits for the recorded launches of one kernel
  * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW, 4 two-head forward sweep, 5 two-head dZ,

@@ -24,22 +24,19 @@ std::mutex g_timing_mu;
 std::vector<TimedLaunch> g_launches;
 }  // namespace
 
-void kt_begin(int id, hipStream_t s) {
-  if (!g_timing) return;
+bool kt_events(int id, hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_timing) return false;
   TimedLaunch t{id, nullptr, nullptr};
-  if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) return;
-  (void)hipEventRecord(t.start, s);
+  if (hipEventCreate(&t.start) != hipSuccess) return false;
+  if (hipEventCreate(&t.stop) != hipSuccess) {
+    (void)hipEventDestroy(t.start);
+    return false;
+  }
+  *start = t.start;
+  *stop = t.stop;
   std::lock_guard<std::mutex> lk(g_timing_mu);
   g_launches.push_back(t);
-}
-void kt_end(int id, hipStream_t s) {
-  if (!g_timing) return;
-  std::lock_guard<std::mutex> lk(g_timing_mu);
-  for (size_t i = g_launches.size(); i-- > 0;)
-    if (g_launches[i].id == id) {
-      (void)hipEventRecord(g_launches[i].stop, s);
-      return;
-    }
+  return true;
 }
 }  // namespace pard2
 

@@ -415,10 +415,8 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
   auto k = fwd_stats_kernel<Cfg>;
   hipError_t e = allow_lds(k, Cfg::LDS_BYTES);
   if (e != hipSuccess) return e;
-  kt_begin(KT_FWD_STATS, s);
-  hipLaunchKernelGGL(k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
+  launch_timed(KT_FWD_STATS, k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
                      (const __bf16*)W, ldW, y, T, d, V, nTt, nVt, ns, out.ms, out.idx, out.zy);
-  kt_end(KT_FWD_STATS, s);
   return hipGetLastError();
 }
 
@@ -476,10 +474,8 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     if (kd) {   // distillation term present: the two-head recompute forms dZ
       if ((e = launch_kd_dz_bf16(H, ldH, W, ldW, *kd, y, lse, g, T, d, V, v0, Kc, dZ, p.Vc, kd->kd_part, s)) != hipSuccess) return e;
     } else {
-      kt_begin(KT_DZ, s);
-      hipLaunchKernelGGL(dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
+      launch_timed(KT_DZ, dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
                          (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
-      kt_end(KT_DZ, s);
     }
     auto sl = dh_k_slices(T, d, Kc);
     if (sl.first > p.kslices) {              // never more slices than the workspace was planned for
@@ -487,8 +483,7 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
       sl.first = ceil_div(Kc, sl.second);
     }
     const int first = c == 0, last = c == p.nchunks - 1;
-    kt_begin(KT_DH, s);
-    hipLaunchKernelGGL(dh_kernel<Cfg>, dim3(nIt * nTt * sl.first), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
+    launch_timed(KT_DH, dh_kernel<Cfg>, dim3(nIt * nTt * sl.first), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
                        (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, sl.first,
                        sl.second, dHacc, dHpart, (__bf16*)dH, first, last);
     if (sl.first > 1) {
@@ -496,13 +491,10 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
       hipLaunchKernelGGL(dh_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, dHpart, sl.first, n4,
                          dHacc, (__bf16*)dH, first, last);
     }
-    kt_end(KT_DH, s);
-    kt_begin(KT_DW, s);
-    hipLaunchKernelGGL(dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
+    launch_timed(KT_DW, dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
                        ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc,
                        dw_f32 ? (__bf16*)((float*)dW + (int64_t)v0 * d) : (__bf16*)dW + (int64_t)v0 * d,
                        accumulate_dW & 1, dw_f32);
-    kt_end(KT_DW, s);
   }
   return hipGetLastError();
 }

@@ -123,10 +123,8 @@ hipError_t launch_inject_fwd(const void* E, const InjectFeats& feats, int64_t ld
   hipError_t e = allow_lds(k, ICfg::LDS_BYTES);
   if (e != hipSuccess) return e;
   const int nIt = ceil_div(d, ICfg::BM), nTt = ceil_div(T, ICfg::BN);
-  kt_begin(KT_INJECT_FWD, s);
-  hipLaunchKernelGGL(k, dim3(nIt * nTt), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, (const __bf16*)E, feats, ldX,
+  launch_timed(KT_INJECT_FWD, k, dim3(nIt * nTt), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, (const __bf16*)E, feats, ldX,
                      (const __bf16*)P, xi, T, d, dt, F, nIt, nTt, (__bf16*)Eout);
-  kt_end(KT_INJECT_FWD, s);
   return hipGetLastError();
 }
 
@@ -139,10 +137,8 @@ hipError_t launch_inject_bwd(const void* dEout, const InjectFeats& feats, int64_
   hipLaunchKernelGGL(inject_gate_kernel, dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, s, (const __bf16*)dEout, xi,
                      n8, d / 8, (__bf16*)dT);
   const int nCt = ceil_div(dt, ICfg::BM), nIt = ceil_div(d, ICfg::BN);
-  kt_begin(KT_INJECT_DP, s);
-  hipLaunchKernelGGL(k, dim3(nCt * nIt * F), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, feats, ldX, (const __bf16*)dT, T,
+  launch_timed(KT_INJECT_DP, k, dim3(nCt * nIt * F), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, feats, ldX, (const __bf16*)dT, T,
                      d, dt, F, nCt, nIt, (__bf16*)dP, accumulate);
-  kt_end(KT_INJECT_DP, s);
   return hipGetLastError();
 }
 

@@ -359,11 +359,9 @@ hipError_t launch_kd_stats_bf16(const void* H, int64_t ldH, const void* W, int64
   auto k = kd_stats_kernel<KdCfg>;
   hipError_t e = allow_lds(k, KdCfg::LDS_BYTES);
   if (e != hipSuccess) return e;
-  kt_begin(KT_KD_STATS, s);
-  hipLaunchKernelGGL(k, dim3(nTt * ns), dim3(KdCfg::NTHREADS), KdCfg::LDS_BYTES, s, (const __bf16*)H, ldH,
+  launch_timed(KT_KD_STATS, k, dim3(nTt * ns), dim3(KdCfg::NTHREADS), KdCfg::LDS_BYTES, s, (const __bf16*)H, ldH,
                      (const __bf16*)W, ldW, (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, T, d, te.d,
                      V, nTt, nVt, ns, out.draft.ms, out.draft.idx, out.draft.zy, out.ms_t, out.a_t, out.zy_t);
-  kt_end(KT_KD_STATS, s);
   return hipGetLastError();
 }
 
@@ -376,11 +374,9 @@ hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t 
   hipError_t e = allow_lds(k, LDS);
   if (e != hipSuccess) return e;
   const int nTt = ceil_div(T, KdCfg::BN), nVtc = Kc / KdCfg::BM;
-  kt_begin(KT_KD_DZ, s);
-  hipLaunchKernelGGL(k, dim3(nTt * nVtc), dim3(KdCfg::NTHREADS), LDS, s, (const __bf16*)H, ldH, (const __bf16*)W, ldW,
+  launch_timed(KT_KD_DZ, k, dim3(nTt * nVtc), dim3(KdCfg::NTHREADS), LDS, s, (const __bf16*)H, ldH, (const __bf16*)W, ldW,
                      (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, lse, te.lse, g, te.beta, T, d, te.d,
                      V, nTt, v0 / KdCfg::BM, nVtc, (__bf16*)dZ, ldz, kd_part);
-  kt_end(KT_KD_DZ, s);
   return hipGetLastError();
 }
 

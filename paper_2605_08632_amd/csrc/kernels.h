@@ -1,6 +1,7 @@
 // Internal launch interface between the C-ABI layer and the kernel translation units.
 // Host functions only; every pointer below is a device pointer.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -9,12 +10,24 @@ namespace pard2 {
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 
 // Optional per-kernel timing (off by default): when switched on through
-// pard2_cat_kernel_timing(), every launch of one of the contraction kernels is
-// bracketed by a pair of HIP events on its stream.
+// pard2_cat_kernel_timing(), every launch of one of the contraction kernels carries a
+// pair of HIP events.
 enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_KD_STATS = 4, KT_KD_DZ = 5,
                 KT_INJECT_FWD = 6, KT_INJECT_DP = 7, KT_COUNT = 8 };
-void kt_begin(int id, hipStream_t s);
-void kt_end(int id, hipStream_t s);
+// false when timing is off; otherwise creates a start/stop pair, records it under `id` and hands it out
+bool kt_events(int id, hipEvent_t* start, hipEvent_t* stop);
+
+// Launch one of the timed kernels.  With timing on, the start/stop events ride on the kernel's own dispatch
+// packet (hipExtLaunchKernelGGL), so no marker packets are queued between kernels and the launch-to-launch
+// gaps stay what they are without timing.
+template <class K, class... Args>
+inline void launch_timed(int id, K kernel, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
+  hipEvent_t e0, e1;
+  if (kt_events(id, &e0, &e1))
+    hipExtLaunchKernelGGL(kernel, grid, block, lds, s, e0, e1, 0, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
 
 // Per-row, per-partial softmax statistics written by the forward sweep:
 // ms[t*P + p] = (max, sum of exp(z - max)) over the p-th vocabulary range, idx = lowest
