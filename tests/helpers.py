@@ -35,19 +35,19 @@ class Problem:
 
 
 def build_problem(B, K, d, V, dtype, seed, p_agree=0.6, fallback="uniform", ragged_frac=0.0,
-                  drop_some=False, stats=None):
+                  drop_some=False, stats=None, w_scale=4.0):
     """Inputs + oracle row statistics.  Regenerates with another seed if a row's top-2 logits
     are too close for an exact argmax comparison (reports how often in `regenerated`)."""
     T = B * K
     p = Problem()
     if stats is not None:                      # stored oracle statistics (full-size workloads)
         attempts = np.asarray(stats["row_attempts"])
-        head = synth.make_head(seed, T, d, V, dtype, row_attempts=attempts)
+        head = synth.make_head(seed, T, d, V, dtype, w_scale, row_attempts=attempts)
         W64 = head.W.astype(np.float64)
         st = stats
     else:
         attempts = np.zeros(T, dtype=np.int64)
-        head = synth.make_head(seed, T, d, V, dtype)
+        head = synth.make_head(seed, T, d, V, dtype, w_scale)
         W64 = head.W.astype(np.float64)
         st = O.head_stats(head.H, None, np.zeros(T, dtype=np.int64), W64=W64)
         for _ in range(8):
@@ -55,7 +55,7 @@ def build_problem(B, K, d, V, dtype, seed, p_agree=0.6, fallback="uniform", ragg
             if len(near) == 0:
                 break
             attempts[near] += 1
-            head = synth.make_head(seed, T, d, V, dtype, row_attempts=attempts)
+            head = synth.make_head(seed, T, d, V, dtype, w_scale, row_attempts=attempts)
             sub = O.head_stats(head.H[near], None, np.zeros(len(near), dtype=np.int64), W64=W64)
             for k in ("m", "lse", "gap", "argmax"):
                 st[k][near] = sub[k]
