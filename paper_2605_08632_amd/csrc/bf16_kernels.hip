@@ -416,7 +416,7 @@ hipError_t launch_fwd_stats_bf16(const void* H, int64_t ldH, const void* W, int6
   hipError_t e = allow_lds(k, Cfg::LDS_BYTES);
   if (e != hipSuccess) return e;
   launch_timed(KT_FWD_STATS, k, dim3(nTt * ns), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H, ldH,
-                     (const __bf16*)W, ldW, y, T, d, V, nTt, nVt, ns, out.ms, out.idx, out.zy);
+               (const __bf16*)W, ldW, y, T, d, V, nTt, nVt, ns, out.ms, out.idx, out.zy);
   return hipGetLastError();
 }
 
@@ -475,7 +475,7 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
       if ((e = launch_kd_dz_bf16(H, ldH, W, ldW, *kd, y, lse, g, T, d, V, v0, Kc, dZ, p.Vc, kd->kd_part, s)) != hipSuccess) return e;
     } else {
       launch_timed(KT_DZ, dz_kernel<Cfg>, dim3(nTt * nVtc), dim3(Cfg::NTHREADS), DZ_LDS, s, (const __bf16*)H, ldH,
-                         (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
+                   (const __bf16*)W, ldW, y, lse, g, T, d, V, nTt, vt0, nVtc, dZ, p.Vc);
     }
     auto sl = dh_k_slices(T, d, Kc);
     if (sl.first > p.kslices) {              // never more slices than the workspace was planned for
@@ -484,17 +484,17 @@ hipError_t launch_bwd_bf16(const BwdPlanBf16& p, const void* H, int64_t ldH, con
     }
     const int first = c == 0, last = c == p.nchunks - 1;
     launch_timed(KT_DH, dh_kernel<Cfg>, dim3(nIt * nTt * sl.first), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s,
-                       (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, sl.first,
-                       sl.second, dHacc, dHpart, (__bf16*)dH, first, last);
+                 (const __bf16*)W + (int64_t)v0 * ldW, ldW, dZ, p.Vc, T, d, nvalid, Kc, nIt, nTt, sl.first,
+                 sl.second, dHacc, dHpart, (__bf16*)dH, first, last);
     if (sl.first > 1) {
       const int64_t n4 = (int64_t)T * d / 4;
       hipLaunchKernelGGL(dh_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, dHpart, sl.first, n4,
                          dHacc, (__bf16*)dH, first, last);
     }
     launch_timed(KT_DW, dw_kernel<Cfg>, dim3(nIt * nVtc), dim3(Cfg::NTHREADS), Cfg::LDS_BYTES, s, (const __bf16*)H,
-                       ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc,
-                       dw_f32 ? (__bf16*)((float*)dW + (int64_t)v0 * d) : (__bf16*)dW + (int64_t)v0 * d,
-                       accumulate_dW & 1, dw_f32);
+                 ldH, dZ, p.Vc, T, d, nvalid, Kc, nIt, nVtc,
+                 dw_f32 ? (__bf16*)((float*)dW + (int64_t)v0 * d) : (__bf16*)dW + (int64_t)v0 * d,
+                 accumulate_dW & 1, dw_f32);
   }
   return hipGetLastError();
 }

@@ -124,7 +124,7 @@ hipError_t launch_inject_fwd(const void* E, const InjectFeats& feats, int64_t ld
   if (e != hipSuccess) return e;
   const int nIt = ceil_div(d, ICfg::BM), nTt = ceil_div(T, ICfg::BN);
   launch_timed(KT_INJECT_FWD, k, dim3(nIt * nTt), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, (const __bf16*)E, feats, ldX,
-                     (const __bf16*)P, xi, T, d, dt, F, nIt, nTt, (__bf16*)Eout);
+               (const __bf16*)P, xi, T, d, dt, F, nIt, nTt, (__bf16*)Eout);
   return hipGetLastError();
 }
 
@@ -138,7 +138,7 @@ hipError_t launch_inject_bwd(const void* dEout, const InjectFeats& feats, int64_
                      n8, d / 8, (__bf16*)dT);
   const int nCt = ceil_div(dt, ICfg::BM), nIt = ceil_div(d, ICfg::BN);
   launch_timed(KT_INJECT_DP, k, dim3(nCt * nIt * F), dim3(ICfg::NTHREADS), ICfg::LDS_BYTES, s, feats, ldX, (const __bf16*)dT, T,
-                     d, dt, F, nCt, nIt, (__bf16*)dP, accumulate);
+               d, dt, F, nCt, nIt, (__bf16*)dP, accumulate);
   return hipGetLastError();
 }
 

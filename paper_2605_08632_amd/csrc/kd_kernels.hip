@@ -360,8 +360,8 @@ hipError_t launch_kd_stats_bf16(const void* H, int64_t ldH, const void* W, int64
   hipError_t e = allow_lds(k, KdCfg::LDS_BYTES);
   if (e != hipSuccess) return e;
   launch_timed(KT_KD_STATS, k, dim3(nTt * ns), dim3(KdCfg::NTHREADS), KdCfg::LDS_BYTES, s, (const __bf16*)H, ldH,
-                     (const __bf16*)W, ldW, (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, T, d, te.d,
-                     V, nTt, nVt, ns, out.draft.ms, out.draft.idx, out.draft.zy, out.ms_t, out.a_t, out.zy_t);
+               (const __bf16*)W, ldW, (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, T, d, te.d,
+               V, nTt, nVt, ns, out.draft.ms, out.draft.idx, out.draft.zy, out.ms_t, out.a_t, out.zy_t);
   return hipGetLastError();
 }
 
@@ -375,8 +375,8 @@ hipError_t launch_kd_dz_bf16(const void* H, int64_t ldH, const void* W, int64_t 
   if (e != hipSuccess) return e;
   const int nTt = ceil_div(T, KdCfg::BN), nVtc = Kc / KdCfg::BM;
   launch_timed(KT_KD_DZ, k, dim3(nTt * nVtc), dim3(KdCfg::NTHREADS), LDS, s, (const __bf16*)H, ldH, (const __bf16*)W, ldW,
-                     (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, lse, te.lse, g, te.beta, T, d, te.d,
-                     V, nTt, v0 / KdCfg::BM, nVtc, (__bf16*)dZ, ldz, kd_part);
+               (const __bf16*)te.H, te.ldH, (const __bf16*)te.W, te.ldW, y, lse, te.lse, g, te.beta, T, d, te.d,
+               V, nTt, v0 / KdCfg::BM, nVtc, (__bf16*)dZ, ldz, kd_part);
   return hipGetLastError();
 }
 
