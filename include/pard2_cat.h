@@ -247,7 +247,8 @@ int pard2_inject_bwd(int32_t T, int32_t d, int32_t dt, int32_t F, const void* dE
  * pard2_cat_kernel_timing_read waits for the recorded launches of one kernel
  * (0 forward sweep, 1 dZ recompute, 2 dH, 3 dW, 4 two-head forward sweep, 5 two-head dZ,
  * 6 injection forward, 7 injection dP)
- * and returns their summed duration in milliseconds and their count.  Host pointers.  Not
+ * and returns their summed duration in milliseconds and their count.  Launches on a stream that is
+ * being captured into a graph are not timed.  Host pointers.  Not
  * thread-safe against concurrent launches from other host threads. */
 int pard2_cat_kernel_timing(int enable);
 int pard2_cat_kernel_timing_read(int kernel, double* total_ms, int64_t* launches);

@@ -24,8 +24,10 @@ std::mutex g_timing_mu;
 std::vector<TimedLaunch> g_launches;
 }  // namespace
 
-bool kt_events(int id, hipEvent_t* start, hipEvent_t* stop) {
+bool kt_events(int id, hipStream_t s, hipEvent_t* start, hipEvent_t* stop) {
   if (!g_timing) return false;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return false;
   TimedLaunch t{id, nullptr, nullptr};
   if (hipEventCreate(&t.start) != hipSuccess) return false;
   if (hipEventCreate(&t.stop) != hipSuccess) {

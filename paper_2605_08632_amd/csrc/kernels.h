@@ -14,8 +14,8 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // pair of HIP events.
 enum KernelId { KT_FWD_STATS = 0, KT_DZ = 1, KT_DH = 2, KT_DW = 3, KT_KD_STATS = 4, KT_KD_DZ = 5,
                 KT_INJECT_FWD = 6, KT_INJECT_DP = 7, KT_COUNT = 8 };
-// false when timing is off; otherwise creates a start/stop pair, records it under `id` and hands it out
-bool kt_events(int id, hipEvent_t* start, hipEvent_t* stop);
+// false when timing is off or the stream is being captured into a graph; otherwise creates a start/stop pair, records it under `id` and hands it out
+bool kt_events(int id, hipStream_t s, hipEvent_t* start, hipEvent_t* stop);
 
 // Launch one of the timed kernels.  With timing on, the start/stop events ride on the kernel's own dispatch
 // packet (hipExtLaunchKernelGGL), so no marker packets are queued between kernels and the launch-to-launch
@@ -23,7 +23,7 @@ bool kt_events(int id, hipEvent_t* start, hipEvent_t* stop);
 template <class K, class... Args>
 inline void launch_timed(int id, K kernel, dim3 grid, dim3 block, unsigned lds, hipStream_t s, Args... args) {
   hipEvent_t e0, e1;
-  if (kt_events(id, &e0, &e1))
+  if (kt_events(id, s, &e0, &e1))
     hipExtLaunchKernelGGL(kernel, grid, block, lds, s, e0, e1, 0, args...);
   else
     hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
