@@ -366,3 +366,31 @@ def test_sharply_peaked_logits(dtype):
     assert np.abs(p.stats["m"]).max() > 80
     _run_case(p, beta=1.0)
     _run_case(p, beta=0.1, external=True, grad_loss=-3.0)
+
+
+def test_block_sharding_equivalence():
+    """How the path would shard over GPUs, shown on one: the draft blocks are cut into two shards, each
+    runs with PARD2_RED_SUM and grad_loss = 1 / N_global; losses divided by N_global and dW summed over
+    the shards, dH concatenated, equal the unsharded MEAN_VALID result (fp32 storage: tight)."""
+    p = Hh.build_problem(22, 8, 72, 900, "fp32", seed=40, ragged_frac=0.3, drop_some=True)
+    b = _binding()
+    H, W, y, vl, conf = Hh.to_device(p)
+    full = b.make_desc(p.T, p.d, p.V, p.B, p.K, b.PARD2_FP32, beta=0.1)
+    out = b.pard2_cat_fwd(full, H, W, y, valid_len=vl)
+    dH, dW = b.pard2_cat_bwd(full, H, W, y, out["lse"], out["w"], valid_len=vl)
+    n_global = int(O.valid_mask(p.y, p.B, p.K, p.valid_len).sum())
+    gl = torch.tensor([1.0 / n_global], dtype=torch.float32, device=H.device)
+    loss_sum, dW_sum, dH_parts = 0.0, torch.zeros_like(dW), []
+    for b0, b1 in ((0, 9), (9, p.B)):
+        r0, r1 = b0 * p.K, b1 * p.K
+        d = b.make_desc(r1 - r0, p.d, p.V, b1 - b0, p.K, b.PARD2_FP32, beta=0.1, reduction=b.PARD2_RED_SUM)
+        o = b.pard2_cat_fwd(d, H[r0:r1].contiguous(), W, y[r0:r1].contiguous(), valid_len=vl[b0:b1].contiguous())
+        gH, gW = b.pard2_cat_bwd(d, H[r0:r1].contiguous(), W, y[r0:r1].contiguous(), o["lse"], o["w"],
+                                 valid_len=vl[b0:b1].contiguous(), grad_loss=gl)
+        loss_sum += o["loss"].item()
+        dW_sum += gW
+        dH_parts.append(gH)
+    torch.cuda.synchronize()
+    assert abs(loss_sum / n_global - out["loss"].item()) < 1e-5 * abs(out["loss"].item())
+    assert (torch.cat(dH_parts) - dH).abs().max() < 1e-5 * dH.abs().max()
+    assert (dW_sum - dW).abs().max() < 1e-5 * dW.abs().max()
