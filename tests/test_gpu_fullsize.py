@@ -81,14 +81,15 @@ def test_fullsize_workload(name):
     print(f"[fullsize] identities ok: <dW,W> {lhs:.6e} <dH,H> {rhs:.6e}", flush=True)
 
 
-def test_fullsize_kd_c2_teacher4096():
-    """The Eq.12 token loss (beta CE + KD) at the headline shape with a teacher head of width 4096,
-    in the launch configuration `bench.py --variant kd` times.  Forward: every row against the oracle
+@pytest.mark.parametrize("name,dt", [("c2_llama1b_bf16", 4096), ("c3_qwen06b_bf16", 4096)])
+def test_fullsize_kd(name, dt):
+    """The Eq.12 token loss (beta CE + KD) at full-size shapes with a teacher head of width 4096,
+    in the launch configuration `bench.py --variant kd` times (the second workload's vocabulary is
+    not a multiple of 256: its last chunk holds a 128-id tile that lies wholly past V).  Forward: every row against the oracle
     (the teacher's logsumexp and KL(p || q) of every row are stored by make_fullsize_stats.py, from
     oracle/ only).  Backward: sampled blocks / vocabulary rows one by one, plus the two identities."""
     from oracle import cat_kd_oracle as KD
     from paper_2605_08632_amd import binding as b
-    name, dt = "c2_llama1b_bf16", 4096
     wl = synth.WORKLOADS[name]
     print(f"[fullsize kd] {name}: T={wl.T} d={wl.d} dt={dt} V={wl.V}", flush=True)
     stats = {k: v for k, v in np.load(os.path.join(GOLDEN, f"fullsize_{name}.npz")).items()}
