@@ -266,30 +266,51 @@ struct GemmNT {
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
     };
-    // the MFMAs with (mi + ni) of the given parity: parity 0 touches every fragment
-    auto mma_par = [&](bf16x8 (&fa)[C::MI], bf16x8 (&fb)[C::NI], int parity) {
-#pragma unroll
-      for (int ni = 0; ni < C::NI; ++ni)
-#pragma unroll
-        for (int mi = 0; mi < C::MI; ++mi)
-          if (((mi + ni) & 1) == parity)
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
-    };
     constexpr int NM = C::MI * C::NI;
 
     // One stage = four k steps.  The instruction order is pinned with scheduling barriers:
-    //   first MFMA of a k step | (next stage's loads,) LDS reads of the next k step | its other MFMAs
-    // so that every LDS read has a k step of MFMAs to land under.  In the last k step half of
+    //   first MFMA of a k step | (next stage's loads,) LDS reads of the next k step interleaved with its
+    //   other MFMAs
+    // so that every LDS read has a k step of MFMAs to land under.  In the last k step most of
     // the MFMAs run, then the barrier (next stage landed for everyone, this stage's buffer free),
-    // then the first reads of the next stage under the remaining MFMAs.
+    // then the first reads of the next stage under the remaining MFMA(s).
 #define PARD2_SB __builtin_amdgcn_sched_barrier(0)
+// The last k step's MFMAs are split around the stage barrier: all but PARD2_AFTER_BARRIER of them are
+// issued before it.  One MFMA after the barrier measured best (it covers the next stage's first LDS
+// reads, and a late barrier leaves every wavefront's loads the longest time to land): 14.95 -> 14.76 ms
+// per step against an even split, 15.05 ms with none.
+#ifndef PARD2_AFTER_BARRIER
+#define PARD2_AFTER_BARRIER 1
+#endif
+#ifndef PARD2_LEAD
+#define PARD2_LEAD 1   /* MFMAs of a k step issued before the next k step's LDS reads */
+#endif
+// Inside a k step the LDS reads of the next k step are spread between this k step's MFMAs (one read,
+// one MFMA, ...) instead of being issued in one burst: all eight wavefronts run the same phase of the
+// loop at the same time, and a burst from each of them queues up at the LDS behind the direct loads'
+// writes.  Spreading measured 14.83 -> 14.42 ms per step (dW, whose operands take two transposing reads
+// per fragment, gains most).  PARD2_INTERLEAVE = LDS reads per MFMA in that pattern; 0 = burst.
+#ifndef PARD2_INTERLEAVE
+#define PARD2_INTERLEAVE 1
+#endif
+#if PARD2_INTERLEAVE > 0
+#define PARD2_MIXSB
+#define PARD2_G(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+#define PARD2_G1 PARD2_G(0x100, PARD2_INTERLEAVE); PARD2_G(0x008, 1)   /* DS reads, then one MFMA */
+#define PARD2_MIX PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G(0x008, 2)
+#else
+#define PARD2_MIXSB PARD2_SB
+#define PARD2_MIX
+#endif
+#define PARD2_LAST_A mma_sel(fa1, fb1, 0, NM - PARD2_AFTER_BARRIER)
+#define PARD2_LAST_B mma_sel(fa1, fb1, NM - PARD2_AFTER_BARRIER, NM)
 #define PARD2_STAGE(ISSUE0, ISSUE1, HAS_NEXT)                                                             \
-  mma_sel(fa0, fb0, 0, 1); PARD2_SB; ISSUE0; read_frags(kt, 1, fa1, fb1); PARD2_SB; mma_sel(fa0, fb0, 1, NM); PARD2_SB; \
-  mma_sel(fa1, fb1, 0, 1); PARD2_SB; ISSUE1; read_frags(kt, 2, fa0, fb0); PARD2_SB; mma_sel(fa1, fb1, 1, NM); PARD2_SB; \
-  mma_sel(fa0, fb0, 0, 1); PARD2_SB;         read_frags(kt, 3, fa1, fb1); PARD2_SB; mma_sel(fa0, fb0, 1, NM); PARD2_SB; \
-  mma_par(fa1, fb1, 0); PARD2_SB; wait_all_and_barrier(); PARD2_SB;                                       \
+  mma_sel(fa0, fb0, 0, PARD2_LEAD); PARD2_SB; ISSUE0; read_frags(kt, 1, fa1, fb1); PARD2_MIXSB; mma_sel(fa0, fb0, PARD2_LEAD, NM); PARD2_MIX; PARD2_SB; \
+  mma_sel(fa1, fb1, 0, PARD2_LEAD); PARD2_SB; ISSUE1; read_frags(kt, 2, fa0, fb0); PARD2_MIXSB; mma_sel(fa1, fb1, PARD2_LEAD, NM); PARD2_MIX; PARD2_SB; \
+  mma_sel(fa0, fb0, 0, PARD2_LEAD); PARD2_SB;         read_frags(kt, 3, fa1, fb1); PARD2_MIXSB; mma_sel(fa0, fb0, PARD2_LEAD, NM); PARD2_MIX; PARD2_SB; \
+  PARD2_LAST_A; PARD2_SB; wait_all_and_barrier(); PARD2_SB;                                               \
   if (HAS_NEXT) read_frags(kt + 1, 0, fa0, fb0);                                                          \
-  PARD2_SB; mma_par(fa1, fb1, 1); PARD2_SB;
+  PARD2_SB; PARD2_LAST_B; PARD2_SB;
 
     if (!prefetched) prefetch();
     wait_all_and_barrier();
@@ -307,6 +328,12 @@ struct GemmNT {
       PARD2_STAGE((void)0, (void)0, false)
     }
 #undef PARD2_STAGE
+#undef PARD2_MIX
+#undef PARD2_MIXSB
+#undef PARD2_G1
+#undef PARD2_G
+#undef PARD2_LAST_A
+#undef PARD2_LAST_B
 #undef PARD2_SB
     // the barrier inside the last stage already separates every wavefront's last LDS read
     // from whatever the caller does with LDS next
