@@ -178,23 +178,16 @@ struct Panel {
     }
   }
 
-  // fragments of k step kk (16 k) of the stage whose panel starts at `p`
-  __device__ __forceinline__ void read(const char* p, int kk, int koff_kc, bf16x8 (&f)[NSUB]) const {
+  // fragment of sub-tile s for k step kk (16 k) of the stage whose panel starts at `p`
+  __device__ __forceinline__ bf16x8 read_one(const char* p, int kk, int koff_kc, int s) const {
     if constexpr (!KM) {
-#pragma unroll
-      for (int s = 0; s < NSUB; ++s)
-        f[s] = *reinterpret_cast<const bf16x8*>(p + rd_base + s * 32 * 128 + koff_kc);
+      return *reinterpret_cast<const bf16x8*>(p + rd_base + s * 32 * 128 + koff_kc);
     } else {
-#pragma unroll
-      for (int s = 0; s < NSUB; ++s) {
-        const char* q = p + rd_base + rd_sub[s] + kk * 16 * 512;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(q));
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-            (__attribute__((address_space(3))) s16x4*)(q + 4 * 512));
-        const __attribute__((ext_vector_type(8))) short v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        f[s] = __builtin_bit_cast(bf16x8, v);
-      }
+      const char* q = p + rd_base + rd_sub[s] + kk * 16 * 512;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(q + 4 * 512));
+      const __attribute__((ext_vector_type(8))) short v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      return __builtin_bit_cast(bf16x8, v);
     }
   }
 };
@@ -250,8 +243,13 @@ struct GemmNT {
     bf16x8 fa0[C::MI], fb0[C::NI], fa1[C::MI], fb1[C::NI];
     auto read_frags = [&](int kt, int kk, bf16x8 (&fa)[C::MI], bf16x8 (&fb)[C::NI]) {
       const char* s = smem + (kt & 1) * C::STAGE_BYTES;
-      pa.read(s, kk, koff[kk], fa);
-      pb.read(s + C::A_PANEL, kk, koff[kk], fb);
+      // in the order the MFMAs of the k step want them: column 0's B fragment, the A fragments, the other
+      // B fragments (LDS reads return in order, so the first MFMA waits for two reads, not for all)
+      fb[0] = pb.read_one(s + C::A_PANEL, kk, koff[kk], 0);
+#pragma unroll
+      for (int i = 0; i < C::MI; ++i) fa[i] = pa.read_one(s, kk, koff[kk], i);
+#pragma unroll
+      for (int i = 1; i < C::NI; ++i) fb[i] = pb.read_one(s + C::A_PANEL, kk, koff[kk], i);
     };
     // MFMAs number lo..hi-1 of the MI x NI grid, numbered column by column in a serpentine (down
     // column 0, up column 1, ...): consecutive MFMAs always share an operand register set, which
