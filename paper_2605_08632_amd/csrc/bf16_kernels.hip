@@ -258,7 +258,9 @@ __global__ __launch_bounds__(C::NTHREADS) void dz_kernel(const __bf16* __restric
     const int t = n0 + r;
     if (t < T) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(smem + r * DZ_PITCH + chunk * 16);
-      *reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8) = v;
+      // streamed out: the chunk (hundreds of MB) is read back only by later kernels, keeping it out of
+      // the L2 leaves the operand panels there (measured: dz 3.78 -> 3.67 ms per step)
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8));
     }
   }
 }

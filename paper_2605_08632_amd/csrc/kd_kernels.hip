@@ -320,7 +320,7 @@ __global__ __launch_bounds__(C::NTHREADS) void kd_dz_kernel(
     if (t < T) {
       u32x4 v = {0u, 0u, 0u, 0u};
       if (live) v = *reinterpret_cast<const u32x4*>(smem + r * KD_DZ_PITCH + chunk * 16);
-      *reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dZ + (int64_t)t * ldz + c0 + chunk * 8));   // streamed out
     }
   }
   // per-row sum_v p (zT - zD) over this tile's ids -> kd_part[tile][t] (tiles past V write nothing)
