@@ -295,7 +295,7 @@ struct GemmNT {
 #define PARD2_MIXSB
 #define PARD2_G(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
 #define PARD2_G1 PARD2_G(0x100, PARD2_INTERLEAVE); PARD2_G(0x008, 1)   /* DS reads, then one MFMA */
-#define PARD2_MIX PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G(0x008, 2)
+#define PARD2_MIX PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1; PARD2_G1   /* MI + NI <= 8 reads */
 #else
 #define PARD2_MIXSB PARD2_SB
 #define PARD2_MIX
