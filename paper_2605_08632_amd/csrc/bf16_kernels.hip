@@ -23,6 +23,10 @@ using Cfg = TileCfg<PARD2_TILE>;
 #ifndef PARD2_CHUNK_TILES
 #define PARD2_CHUNK_TILES 64
 #endif
+// workgroups the forward sweep aims for (token tiles x vocabulary ranges)
+#ifndef PARD2_FWD_WGS
+#define PARD2_FWD_WGS 256
+#endif
 #ifndef PARD2_BAND_FWD
 #define PARD2_BAND_FWD 8
 #endif
@@ -406,7 +410,7 @@ static hipError_t allow_lds(K kernel, int bytes) {
 int fwd_num_partials_bf16(int T, int V) {
   const int nTt = ceil_div(T, Cfg::BN), nVt = ceil_div(V, Cfg::BM);
   // enough vocabulary ranges to give every compute unit a workgroup, never more than tiles
-  int ns = ceil_div(256, nTt);
+  int ns = ceil_div(PARD2_FWD_WGS, nTt);
   ns = ns < 1 ? 1 : ns;
   return ns > nVt ? nVt : ns;
 }
